@@ -1,0 +1,98 @@
+"""Time-sliced EST execution on simulated workers, on the CPU.  TEST INFRASTRUCTURE ONLY.
+
+Follows the paper's §3.2 step by step: every worker owns one live copy of the
+small per-EST state (RNG state, BatchNorm running statistics) and an arena of
+context slots, one per EST it hosts.  Within a global step a worker runs its
+ESTs one after the other; for each it restores the EST's context into the live
+state, lets the EST's mini-batch touch the live state, stages the EST's
+gradients in its slot, and saves the live state back.  When every EST has run,
+gradients are all-reduced among ESTs by *virtual rank* (§3.3 D1), never by
+worker or slot, and the shared replica is updated once.
+
+Pinned against ddp_reference.DDPReference (N ranks that never switch): every
+grouping has to give the same bits.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import dropout_mask, ring_order_reduce, sgd_momentum
+
+
+class ESTModel:
+    def __init__(self, n_logical: int, worker_of_est: Sequence[int], slot_of_est: Sequence[int],
+                 buckets: Sequence[Tuple[int, int]], n_params: int, chunk_align: int,
+                 lr: float, momentum: float, p0: np.ndarray,
+                 philox_seeds: Optional[Sequence[int]] = None,
+                 bn0: Optional[np.ndarray] = None):
+        self.N = n_logical
+        self.worker_of_est = list(worker_of_est)
+        self.slot_of_est = list(slot_of_est)
+        self.buckets = list(buckets)
+        self.A = chunk_align
+        self.lr, self.mu = lr, momentum
+        self.p = np.array(p0, dtype=np.float32, copy=True)
+        self.v = np.zeros(n_params, dtype=np.float32)
+        self.avg = np.zeros(n_params, dtype=np.float32)
+        n_workers = max(self.worker_of_est) + 1
+        per_worker = [sum(1 for w in self.worker_of_est if w == i) for i in range(n_workers)]
+        self.has_rng = philox_seeds is not None
+        self.has_bn = bn0 is not None
+        bn_len = bn0.shape[1] if self.has_bn else 0
+        # live state: one per worker; deliberately filled with junk so that a
+        # missing restore shows
+        self.live_rng = [np.full(2, 0xDEADBEEF, dtype=np.uint64) for _ in range(n_workers)]
+        self.live_bn = [np.full(bn_len, np.nan, dtype=np.float32) for _ in range(n_workers)]
+        # arenas: slot -> context
+        self.slot_rng = [np.zeros((k, 2), dtype=np.uint64) for k in per_worker]
+        self.slot_bn = [np.zeros((k, bn_len), dtype=np.float32) for k in per_worker]
+        self.slot_grad = [[[None] * len(self.buckets) for _ in range(k)] for k in per_worker]
+        for e in range(self.N):
+            w, s = self.worker_of_est[e], self.slot_of_est[e]
+            if self.has_rng:
+                self.slot_rng[w][s] = (philox_seeds[e], 0)
+            if self.has_bn:
+                self.slot_bn[w][s] = bn0[e]
+
+    def ctx_restore(self, e: int) -> None:
+        w, s = self.worker_of_est[e], self.slot_of_est[e]
+        self.live_rng[w][:] = self.slot_rng[w][s]
+        self.live_bn[w][:] = self.slot_bn[w][s]
+
+    def ctx_save(self, e: int) -> None:
+        w, s = self.worker_of_est[e], self.slot_of_est[e]
+        self.slot_rng[w][s] = self.live_rng[w]
+        self.slot_bn[w][s] = self.live_bn[w]
+
+    def accumulate(self, e: int, b: int, grad: np.ndarray) -> None:
+        w, s = self.worker_of_est[e], self.slot_of_est[e]
+        self.slot_grad[w][s][b] = np.array(grad, dtype=np.float32, copy=True)
+
+    def local_step(self, e: int, mask_n: int = 0, p_drop: float = 0.0,
+                   bn_delta: Optional[np.ndarray] = None) -> Optional[np.ndarray]:
+        """The part of EST e's mini-batch that touches live state on its worker."""
+        w = self.worker_of_est[e]
+        mask = None
+        if self.has_rng and mask_n:
+            mask = dropout_mask(self.live_rng[w], mask_n, p_drop)
+        if self.has_bn and bn_delta is not None:
+            self.live_bn[w][:] = self.live_bn[w] + bn_delta.astype(np.float32)
+        return mask
+
+    def reduce_and_update(self) -> None:
+        for b, (off, ln) in enumerate(self.buckets):
+            ranks = np.empty((self.N, ln), dtype=np.float32)
+            for e in range(self.N):                      # row index = virtual rank
+                w, s = self.worker_of_est[e], self.slot_of_est[e]
+                ranks[e] = self.slot_grad[w][s][b]
+                self.slot_grad[w][s][b] = None
+            self.avg[off:off + ln] = ring_order_reduce(ranks, self.A, clobber=True)
+        sgd_momentum(self.p, self.v, self.avg, self.lr, self.mu)
+
+    def est_rng(self, e: int) -> np.ndarray:
+        return self.slot_rng[self.worker_of_est[e]][self.slot_of_est[e]]
+
+    def est_bn(self, e: int) -> np.ndarray:
+        return self.slot_bn[self.worker_of_est[e]][self.slot_of_est[e]]
