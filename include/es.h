@@ -1,0 +1,243 @@
+/*
+ * libes — the EasyScaleThread (EST) step on one AMD MI355X (gfx950).
+ *
+ * N logical data-parallel workers (ESTs) are time-sliced on one device.  Each
+ * EST has a context: its gradient buckets, plus small determinism-critical
+ * state such as an RNG state and BatchNorm running statistics (paper §3.2
+ * "Context switching", §3.3 "implicit framework state").  Parameters and
+ * optimizer state exist once and are updated once per global step (§3.2).
+ * At the end of a global step the N gradient sets are reduced in the fixed
+ * order an N-rank ring all-reduce would use, each EST acting under its
+ * constant virtual communication rank, bucket by bucket with the recorded
+ * bucket mapping (§3.3, level D1), so the result does not depend on how ESTs
+ * are grouped onto physical workers.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every pointer argument is marked HOST or DEVICE.  DEVICE
+ *    pointers are ordinary HIP device addresses on the device that was current
+ *    at es_init.  fp32 DEVICE buffers must be 16-byte aligned.
+ *  - Every call returns ES_OK (0) or a negative es_status; nothing throws or
+ *    aborts.  Arguments are validated synchronously before anything is
+ *    enqueued; a call that fails validation enqueues nothing.  GPU work is
+ *    enqueued asynchronously on the streams given to es_set_streams; errors of
+ *    asynchronous work surface at es_sync.
+ *  - `est` is always the EST's virtual rank in [0, n_logical), never a
+ *    physical slot.
+ *  - The library owns the context arenas (allocated with hipMalloc at es_init /
+ *    es_set_grouping, released at es_destroy).  Parameters, momentum, averaged
+ *    gradient, gradient sources, live state tensors and masks belong to the
+ *    caller and must stay valid until the work enqueued on them has finished.
+ *  - A handle is not thread-safe; calls on one handle must not overlap.
+ *  - No kernel of this library uses atomics, and every floating-point result
+ *    is independent of grid size and launch configuration.
+ */
+#ifndef ES_H
+#define ES_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct es_handle es_handle;           /* opaque, owned by the library */
+
+typedef enum es_status {
+    ES_OK      = 0,
+    ES_EINVAL  = -1,   /* null / out-of-range / misaligned argument, bad layout */
+    ES_ESTATE  = -2,   /* call not valid now: bucket accumulated twice, reduce before all
+                          (est, bucket) pairs were accumulated, live state not bound, ... */
+    ES_ENOMEM  = -3,   /* host or device allocation failed */
+    ES_EHIP    = -4    /* a HIP call failed; see es_last_hip_error */
+} es_status;
+
+/* One gradient bucket: a range of the flat fp32 parameter space. */
+typedef struct es_bucket {
+    uint64_t offset_elems;
+    uint64_t len_elems;            /* may be 0 */
+} es_bucket;
+
+/*
+ * The recorded gradient-bucket mapping (paper §3.3: the mapping is stored and
+ * reinstated, never rebuilt) and the shape of the small per-EST state.
+ *   buckets          HOST array; ranges must be disjoint, ascending and cover
+ *                    [0, n_params) exactly.  Copied by es_init.
+ *   chunk_align      >= 1.  Each bucket of length L is cut into n_logical ring
+ *                    chunks of length roundup(ceil(L / n_logical), chunk_align);
+ *                    trailing chunks may be short or empty.  4 keeps every
+ *                    16-byte vector inside one chunk when bucket offsets are
+ *                    multiples of 4; any value is correct.
+ *   state_seg_bytes  HOST array of n_state_segs sizes (> 0): the live small
+ *                    state tensors of one worker, e.g. a 16-byte Philox state
+ *                    and the running mean / variance of every BatchNorm layer.
+ *                    Copied by es_init.
+ */
+typedef struct es_bucket_layout {
+    uint64_t         n_params;
+    uint32_t         n_buckets;
+    const es_bucket* buckets;
+    uint32_t         chunk_align;
+    uint32_t         n_state_segs;
+    const uint64_t*  state_seg_bytes;
+} es_bucket_layout;
+
+/*
+ * Create a job with n_logical ESTs (1 .. 65535) on the current HIP device.
+ * Starts with one simulated worker that holds all ESTs (slot = rank), all
+ * streams = the null stream, and no live state bound.
+ * Allocates n_logical gradient slots of n_params floats and n_logical small
+ * context slots on the device.  *out is set only on success.
+ */
+int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* layout);
+
+/* Waits for the handle's streams, frees all device and host memory of the handle. */
+int es_destroy(es_handle* h);
+
+/*
+ * Streams (HOST values of hipStream_t; NULL = the null stream).
+ *   main   the EST's own compute, es_dropout_mask, es_ring_order_reduce,
+ *          es_sgd_step, es_reduce_sgd_step
+ *   ctx    es_ctx_save / es_ctx_restore / es_ctx_switch (small state)
+ *   stage  es_accumulate (bulk gradient copies, paper §3.2: overlapped with the
+ *          next EST's compute)
+ * Ordering is wired with events inside the calls: a restore starts after the
+ * work already enqueued on main and is visible to work enqueued on main
+ * afterwards; a save or an accumulate starts after the work already enqueued
+ * on main; the reduce starts after every accumulate of the step.  If all three
+ * are the same stream no events are used.  Must not be called while work of
+ * this handle is in flight (call es_sync first).
+ */
+int es_set_streams(es_handle* h, void* main, void* ctx, void* stage);
+
+/*
+ * Map ESTs onto simulated physical workers (paper §3.2: any EST can be placed
+ * on any worker; §3.3 D1: results must not depend on the placement).
+ *   worker_of_est, slot_of_est  HOST arrays of n_logical entries; (worker, slot)
+ *   pairs must be distinct, workers 0..n_workers-1 each non-empty, and slots of
+ *   a worker dense in [0, #ESTs of that worker).
+ * Every worker gets its own arena allocation.  The small-state contexts of all
+ * ESTs are carried over to their new slots (device copies); staged gradients
+ * are not, so this must be called between global steps (ES_ESTATE otherwise).
+ * Live-state bindings are dropped.  Synchronises the handle's streams.
+ */
+int es_set_grouping(es_handle* h, uint32_t n_workers,
+                    const uint32_t* worker_of_est, const uint32_t* slot_of_est);
+
+/*
+ * Bind the live small-state tensors of one worker.
+ *   live_ptrs  HOST array of n_state_segs DEVICE pointers; tensor j holds
+ *              state_seg_bytes[j] bytes.  Any alignment is accepted (16-byte
+ *              aligned tensors whose size is a multiple of 16 take the vector
+ *              path).  Tensors must not overlap.
+ */
+int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs);
+
+/* slot[est] -> live tensors of est's worker.  One batched copy kernel on the ctx stream. */
+int es_ctx_restore(es_handle* h, uint32_t est);
+/*
+ * live tensors of est's worker -> slot[est].  One batched copy kernel on the ctx stream.
+ * Work enqueued on main afterwards is NOT made to wait for the save (so the
+ * save of a step's last EST overlaps with the reduce): the live tensors must
+ * not be written again before the next es_ctx_restore / es_ctx_switch on that
+ * worker, or es_sync.
+ */
+int es_ctx_save(es_handle* h, uint32_t est);
+/*
+ * Save est_out and restore est_in (same worker, est_out != est_in) in a single
+ * kernel: an EST switch at a mini-batch boundary (paper §3.2).  Equivalent to
+ * es_ctx_save(est_out) followed by es_ctx_restore(est_in).
+ */
+int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in);
+
+/*
+ * Stage one gradient bucket of one EST in its context (the paper's per-EST
+ * gradient copy, §3.2 / §5.1.3; here device-to-device because all N gradient
+ * sets fit in HBM).
+ *   d_grad_bucket  DEVICE, len_elems floats of that bucket, 4-byte aligned
+ *                  (16-byte aligned sources take the vector path).  If it
+ *                  equals es_grad_slot(est, bucket) nothing is copied and the
+ *                  bucket is only marked as present (zero-copy production).
+ * Exactly one call per (est, bucket) per global step: a second one returns
+ * ES_ESTATE.  The source must stay unmodified until the copy has run (e.g.
+ * until es_stage_fence or es_sync).
+ */
+int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_grad_bucket);
+
+/* DEVICE address of est's slot for `bucket` (NULL on bad arguments).  Changes at es_set_grouping. */
+float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket);
+
+/* Makes work enqueued on main after this call wait for all staging copies enqueued so far. */
+int es_stage_fence(es_handle* h);
+
+/*
+ * Dropout keep-mask from the live RNG state of est's worker (paper §3.3: the
+ * Dropout operator depends on RNG state, which therefore is EST context).
+ *   state_seg  index of a 16-byte state segment {uint64 seed, uint64 offset},
+ *              whose live tensor must be 8-byte aligned
+ *   d_mask     DEVICE, n bytes, any alignment
+ *   p          drop probability in [0, 1]; threshold = floor(p * 2^32)
+ * Byte j becomes 1 (keep) iff word (j mod 4) of Philox4x32-10 (Salmon et al.,
+ * SC'11) with key = seed and counter = (offset + j/4, 0, 0) is >= threshold;
+ * then offset += ceil(n/4).  Runs on main.
+ */
+int es_dropout_mask(es_handle* h, uint32_t est, uint32_t state_seg,
+                    uint8_t* d_mask, uint64_t n, double p);
+
+/*
+ * EST-aware gradient all-reduce on one device (paper §3.3 D1, §4 ElasticDDP).
+ * For every bucket, ring chunk c and element i of that chunk:
+ *     avg[i] = (((g[c][i] + g[c+1][i]) + ...) + g[c+N-1][i]) / (float)N
+ * ranks taken mod N, every + and the / rounded to fp32 (IEEE, denormals kept):
+ * the association order of an N-rank ring reduce-scatter, then the average.
+ *   d_avg_grad  DEVICE, n_params floats, 16-byte aligned; written once (all
+ *               ranks of a real ring would hold this same vector).
+ * Requires every (est, bucket) to have been accumulated exactly once since the
+ * last reduce (ES_ESTATE otherwise) and starts a new global step.
+ */
+int es_ring_order_reduce(es_handle* h, float* d_avg_grad);
+
+/*
+ * SGD with momentum on the single shared replica (paper §3.2):
+ *     v <- mu*v + g ;  p <- p - lr*v
+ * every multiply and add rounded to fp32 on its own (no fused multiply-add).
+ * All DEVICE, n_params floats, 16-byte aligned; p and v updated in place.
+ */
+int es_sgd_step(es_handle* h, float* d_param, float* d_momentum,
+                const float* d_avg_grad, float lr, float mu);
+
+/*
+ * es_ring_order_reduce and es_sgd_step in one kernel: same bits, without the
+ * round trip of the averaged gradient through HBM.  d_avg_grad may be NULL
+ * (not stored) or a DEVICE buffer of n_params floats.
+ */
+int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
+                       float* d_avg_grad, float lr, float mu);
+
+/* Blocks until all streams of the handle are idle; returns ES_EHIP if any work failed. */
+int es_sync(es_handle* h);
+
+/*
+ * Launch-shape options (never change results).  Names:
+ *   "reduce_tile_elems"   elements of one bucket chunk handled by one workgroup
+ *                         (multiple of 4, 256 .. 65536)
+ *   "reduce_unroll"       16-byte vectors per lane in flight per rank (1, 2, 4)
+ *   "reduce_rank_batch"   ranks loaded before their adds are issued (1, 2, 4, 8, 16)
+ *   "nontemporal"         0/1: streaming hint on gradient loads
+ * Returns ES_EINVAL for unknown names or values.
+ */
+int es_set_option(es_handle* h, const char* name, int64_t value);
+int es_get_option(es_handle* h, const char* name, int64_t* value);
+
+/* Sizes the library derived from the layout (HOST out pointers, each may be NULL). */
+int es_query(es_handle* h, uint64_t* n_params, uint32_t* n_buckets, uint64_t* ctx_bytes,
+             uint32_t* n_workers, uint64_t* n_reduce_tiles);
+
+int         es_last_hip_error(es_handle* h);      /* hipError_t of the last ES_EHIP, else 0 */
+const char* es_strerror(int status);
+const char* es_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ES_H */

@@ -1,0 +1,171 @@
+"""ctypes binding of libes (include/es.h): same names, argument marshalling only.
+
+Every function takes the raw handle / device addresses as integers
+(``tensor.data_ptr()``, ``stream.cuda_stream``) and returns the library's
+status code; ``check`` turns a negative status into an exception.  Nothing is
+computed here.  If the built library is missing the import of ``lib()`` fails
+loudly: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+from . import build as _build
+
+ES_OK, ES_EINVAL, ES_ESTATE, ES_ENOMEM, ES_EHIP = 0, -1, -2, -3, -4
+
+
+class EsBucket(ctypes.Structure):
+    _fields_ = [("offset_elems", ctypes.c_uint64), ("len_elems", ctypes.c_uint64)]
+
+
+class EsBucketLayout(ctypes.Structure):
+    _fields_ = [("n_params", ctypes.c_uint64),
+                ("n_buckets", ctypes.c_uint32),
+                ("buckets", ctypes.POINTER(EsBucket)),
+                ("chunk_align", ctypes.c_uint32),
+                ("n_state_segs", ctypes.c_uint32),
+                ("state_seg_bytes", ctypes.POINTER(ctypes.c_uint64))]
+
+
+class EsError(RuntimeError):
+    def __init__(self, status: int, where: str, hip: int = 0):
+        self.status = status
+        self.hip = hip
+        msg = lib().es_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hipError {hip})" if hip else ")"))
+
+
+_lib: Optional[ctypes.CDLL] = None
+
+_VP = ctypes.c_void_p
+_SIGS = {
+    "es_init": (ctypes.c_int, [ctypes.POINTER(_VP), ctypes.c_uint32, ctypes.POINTER(EsBucketLayout)]),
+    "es_destroy": (ctypes.c_int, [_VP]),
+    "es_set_streams": (ctypes.c_int, [_VP, _VP, _VP, _VP]),
+    "es_set_grouping": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32),
+                                       ctypes.POINTER(ctypes.c_uint32)]),
+    "es_bind_live_state": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.POINTER(_VP)]),
+    "es_ctx_restore": (ctypes.c_int, [_VP, ctypes.c_uint32]),
+    "es_ctx_save": (ctypes.c_int, [_VP, ctypes.c_uint32]),
+    "es_ctx_switch": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
+    "es_accumulate": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP]),
+    "es_grad_slot": (_VP, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
+    "es_stage_fence": (ctypes.c_int, [_VP]),
+    "es_dropout_mask": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP,
+                                       ctypes.c_uint64, ctypes.c_double]),
+    "es_ring_order_reduce": (ctypes.c_int, [_VP, _VP]),
+    "es_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
+    "es_reduce_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
+    "es_sync": (ctypes.c_int, [_VP]),
+    "es_set_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.c_int64]),
+    "es_get_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]),
+    "es_query": (ctypes.c_int, [_VP, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
+                                ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
+                                ctypes.POINTER(ctypes.c_uint64)]),
+    "es_last_hip_error": (ctypes.c_int, [_VP]),
+    "es_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+    "es_version": (ctypes.c_char_p, []),
+}
+EXPORTS = tuple(_SIGS)
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded libes.so.  Built first only if no built library exists."""
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build(force=True)
+        L = ctypes.CDLL(path)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(L, name)          # AttributeError if a declared symbol is missing
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def check(status: int, where: str, h: Optional[int] = None) -> int:
+    if status < 0:
+        hip = lib().es_last_hip_error(h) if (h and status == ES_EHIP) else 0
+        raise EsError(status, where, hip)
+    return status
+
+
+# ---- thin wrappers: one per entry point, same names ---------------------------------
+
+def es_init(n_logical: int, n_params: int, buckets: Sequence[Tuple[int, int]], chunk_align: int,
+            state_seg_bytes: Sequence[int] = ()) -> Tuple[int, int]:
+    """Returns (status, handle)."""
+    arr = (EsBucket * max(1, len(buckets)))(*[EsBucket(o, l) for o, l in buckets])
+    segs = (ctypes.c_uint64 * max(1, len(state_seg_bytes)))(*state_seg_bytes)
+    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs)
+    h = _VP()
+    st = lib().es_init(ctypes.byref(h), n_logical, ctypes.byref(lay))
+    return st, (h.value or 0)
+
+
+def es_destroy(h): return lib().es_destroy(h)
+def es_set_streams(h, main, ctx, stage): return lib().es_set_streams(h, main, ctx, stage)
+
+
+def es_set_grouping(h, worker_of_est: Sequence[int], slot_of_est: Sequence[int]) -> int:
+    n = len(worker_of_est)
+    w = (ctypes.c_uint32 * n)(*worker_of_est)
+    s = (ctypes.c_uint32 * n)(*slot_of_est)
+    return lib().es_set_grouping(h, (max(worker_of_est) + 1) if n else 0, w, s)
+
+
+def es_bind_live_state(h, worker: int, live_ptrs: Sequence[int]) -> int:
+    arr = (_VP * max(1, len(live_ptrs)))(*live_ptrs)
+    return lib().es_bind_live_state(h, worker, arr)
+
+
+def es_ctx_restore(h, est): return lib().es_ctx_restore(h, est)
+def es_ctx_save(h, est): return lib().es_ctx_save(h, est)
+def es_ctx_switch(h, est_out, est_in): return lib().es_ctx_switch(h, est_out, est_in)
+def es_accumulate(h, est, bucket, d_grad): return lib().es_accumulate(h, est, bucket, d_grad)
+def es_grad_slot(h, est, bucket): return lib().es_grad_slot(h, est, bucket) or 0
+def es_stage_fence(h): return lib().es_stage_fence(h)
+
+
+def es_dropout_mask(h, est, state_seg, d_mask, n, p):
+    return lib().es_dropout_mask(h, est, state_seg, d_mask, n, p)
+
+
+def es_ring_order_reduce(h, d_avg): return lib().es_ring_order_reduce(h, d_avg)
+
+
+def es_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
+    return lib().es_sgd_step(h, d_param, d_momentum, d_avg, lr, mu)
+
+
+def es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
+    return lib().es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu)
+
+
+def es_sync(h): return lib().es_sync(h)
+def es_set_option(h, name: str, value: int): return lib().es_set_option(h, name.encode(), value)
+
+
+def es_get_option(h, name: str) -> Tuple[int, int]:
+    v = ctypes.c_int64()
+    st = lib().es_get_option(h, name.encode(), ctypes.byref(v))
+    return st, v.value
+
+
+def es_query(h):
+    """Returns (status, dict)."""
+    P, nb, cb, nw, nt = (ctypes.c_uint64(), ctypes.c_uint32(), ctypes.c_uint64(),
+                         ctypes.c_uint32(), ctypes.c_uint64())
+    st = lib().es_query(h, ctypes.byref(P), ctypes.byref(nb), ctypes.byref(cb),
+                        ctypes.byref(nw), ctypes.byref(nt))
+    return st, dict(n_params=P.value, n_buckets=nb.value, ctx_bytes=cb.value,
+                    n_workers=nw.value, n_reduce_tiles=nt.value)
+
+
+def es_last_hip_error(h): return lib().es_last_hip_error(h)
+def es_strerror(status): return lib().es_strerror(status).decode()
+def es_version(): return lib().es_version().decode()

@@ -1,0 +1,53 @@
+"""Builds libes.so (HIP, gfx950 only) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libes.so")
+SOURCES = [os.path.join(CSRC, "es_kernels.hip"), os.path.join(CSRC, "es_api.cpp")]
+HEADERS = [os.path.join(CSRC, "es_internal.h"), os.path.join(ROOT, "include", "es.h")]
+
+# -ffp-contract=off: no fused multiply-add may be formed (bit-exact SGD update)
+# -fhip-fp32-correctly-rounded-divide-sqrt: IEEE division for the /N
+# -fno-gpu-flush-denormals-to-zero: fp32 denormals are kept
+# packed-fp32 instructions are switched off for the device code
+FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off", "-fhip-fp32-correctly-rounded-divide-sqrt",
+    "-fno-gpu-flush-denormals-to-zero", "-fno-fast-math",
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-command-line-argument",
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
+]
+
+
+def hipcc() -> str:
+    for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if c and (os.path.sep not in c or os.path.exists(c)):
+            return c
+    return "hipcc"
+
+
+def stale() -> bool:
+    if not os.path.exists(LIB):
+        return True
+    t = os.path.getmtime(LIB)
+    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS + [os.path.abspath(__file__)])
+
+
+def build(force: bool = True, verbose: bool = False) -> str:
+    if force or stale():
+        cmd = [hipcc(), *FLAGS, *SOURCES, "-o", LIB]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, verbose=True))

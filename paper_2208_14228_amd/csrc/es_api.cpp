@@ -1,0 +1,576 @@
+// Host runtime and C boundary of libes (declared in include/es.h).
+//
+// Host side only: argument validation, the ring-chunk tile table, the
+// rank -> slot pointer table, context piece tables, stream/event wiring and
+// per-step bookkeeping.  All data movement and arithmetic is done by the
+// kernels in es_kernels.hip.
+#include "es.h"
+#include "es_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace es;
+
+namespace {
+
+constexpr uint64_t kSlotAlignBytes = 256;
+
+struct Worker {
+    uint32_t n_slots = 0;
+    float* grad_arena = nullptr;        // n_slots * grad_stride floats
+    uint8_t* ctx_arena = nullptr;       // n_slots * ctx_stride bytes
+    std::vector<void*> live;            // bound live tensors (device addresses)
+    Piece* d_pieces = nullptr;
+    uint32_t n_pieces = 0;
+    bool bound = false;
+};
+
+}  // namespace
+
+struct es_handle {
+    int device = 0;
+    uint32_t N = 0;
+    uint64_t P = 0;
+    uint32_t A = 1;
+    std::vector<es_bucket> buckets;
+    std::vector<uint64_t> seg_bytes, seg_off;   // seg_off: byte offset inside a context slot
+    uint64_t ctx_bytes = 0;                     // payload of one context slot (16-byte padded segments)
+    uint64_t ctx_stride = 0;                    // bytes between context slots
+    uint64_t grad_stride = 0;                   // floats between gradient slots
+
+    std::vector<uint32_t> worker_of, slot_of;
+    std::vector<Worker> workers;
+
+    Tile* d_tiles = nullptr;
+    uint32_t n_tiles = 0;
+    const float** d_slots = nullptr;            // N device pointers, by virtual rank
+
+    std::vector<uint8_t> accumulated;           // [est * n_buckets + bucket]
+    uint64_t n_accumulated = 0;
+
+    hipStream_t s_main = nullptr, s_ctx = nullptr, s_stage = nullptr;
+    hipEvent_t ev_main = nullptr, ev_ctx = nullptr, ev_stage = nullptr;
+    bool stage_pending = false;                 // staging copies enqueued since the last fence
+
+    uint32_t tile_elems = 4096;
+    ReduceShape shape{1, 8, 1};
+
+    int last_hip = 0;
+};
+
+namespace {
+
+int hip_fail(es_handle* h, hipError_t e)
+{
+    if (h) h->last_hip = (int)e;
+    return ES_EHIP;
+}
+
+#define ES_HIP(h, call)                                  \
+    do {                                                 \
+        hipError_t e__ = (call);                         \
+        if (e__ != hipSuccess) return hip_fail((h), e__); \
+    } while (0)
+
+uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+float* slot_base(const es_handle* h, uint32_t est)
+{
+    const Worker& w = h->workers[h->worker_of[est]];
+    return w.grad_arena + (uint64_t)h->slot_of[est] * h->grad_stride;
+}
+
+uint8_t* ctx_base(const es_handle* h, uint32_t est)
+{
+    const Worker& w = h->workers[h->worker_of[est]];
+    return w.ctx_arena + (uint64_t)h->slot_of[est] * h->ctx_stride;
+}
+
+void free_worker(Worker& w)
+{
+    if (w.grad_arena) (void)hipFree(w.grad_arena);
+    if (w.ctx_arena) (void)hipFree(w.ctx_arena);
+    if (w.d_pieces) (void)hipFree(w.d_pieces);
+    w = Worker{};
+}
+
+int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
+{
+    w.n_slots = n_slots;
+    const uint64_t gbytes = (uint64_t)n_slots * h->grad_stride * sizeof(float);
+    const uint64_t cbytes = (uint64_t)n_slots * h->ctx_stride;
+    if (gbytes) {
+        hipError_t e = hipMalloc((void**)&w.grad_arena, gbytes);
+        if (e != hipSuccess) { h->last_hip = (int)e; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
+    }
+    if (cbytes) {
+        hipError_t e = hipMalloc((void**)&w.ctx_arena, cbytes);
+        if (e != hipSuccess) { h->last_hip = (int)e; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
+        e = hipMemset(w.ctx_arena, 0, cbytes);
+        if (e != hipSuccess) return hip_fail(h, e);
+    }
+    return ES_OK;
+}
+
+// Ring-chunk tile table for the current tile size.  Chunk c of a bucket of
+// length L covers [min(L, c*CL), min(L, (c+1)*CL)), CL = roundup(ceil(L/N), A).
+int build_tiles(es_handle* h)
+{
+    std::vector<Tile> tiles;
+    const uint64_t T = h->tile_elems;
+    for (const es_bucket& b : h->buckets) {
+        const uint64_t L = b.len_elems;
+        if (L == 0) continue;
+        const uint64_t CL = round_up((L + h->N - 1) / h->N, h->A);
+        for (uint32_t c = 0; c < h->N; ++c) {
+            const uint64_t lo = std::min<uint64_t>(L, (uint64_t)c * CL);
+            const uint64_t hi = std::min<uint64_t>(L, lo + CL);
+            for (uint64_t a = lo; a < hi; a += T) {
+                Tile t;
+                t.off = b.offset_elems + a;
+                t.len = (uint32_t)std::min<uint64_t>(T, hi - a);
+                t.rank0 = c;
+                tiles.push_back(t);
+            }
+        }
+    }
+    if (tiles.size() > 0x7fffffffull) return ES_EINVAL;
+    if (h->d_tiles) { (void)hipFree(h->d_tiles); h->d_tiles = nullptr; }
+    h->n_tiles = (uint32_t)tiles.size();
+    if (h->n_tiles) {
+        ES_HIP(h, hipMalloc((void**)&h->d_tiles, tiles.size() * sizeof(Tile)));
+        ES_HIP(h, hipMemcpy(h->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
+    }
+    return ES_OK;
+}
+
+int upload_slot_table(es_handle* h)
+{
+    std::vector<const float*> ptrs(h->N);
+    for (uint32_t e = 0; e < h->N; ++e) ptrs[e] = slot_base(h, e);
+    if (!h->d_slots) ES_HIP(h, hipMalloc((void**)&h->d_slots, h->N * sizeof(float*)));
+    ES_HIP(h, hipMemcpy((void*)h->d_slots, ptrs.data(), h->N * sizeof(float*), hipMemcpyHostToDevice));
+    return ES_OK;
+}
+
+bool valid_grouping(uint32_t N, uint32_t n_workers, const uint32_t* wo, const uint32_t* so,
+                    std::vector<uint32_t>& counts)
+{
+    if (n_workers == 0 || n_workers > N) return false;
+    counts.assign(n_workers, 0);
+    for (uint32_t e = 0; e < N; ++e) {
+        if (wo[e] >= n_workers) return false;
+        counts[wo[e]]++;
+    }
+    std::vector<std::vector<uint8_t>> seen(n_workers);
+    for (uint32_t w = 0; w < n_workers; ++w) {
+        if (counts[w] == 0) return false;
+        seen[w].assign(counts[w], 0);
+    }
+    for (uint32_t e = 0; e < N; ++e) {
+        if (so[e] >= counts[wo[e]] || seen[wo[e]][so[e]]) return false;
+        seen[wo[e]][so[e]] = 1;
+    }
+    return true;
+}
+
+// Ordering helpers.  `from` must have finished what is enqueued on it so far
+// before work enqueued on `to` after this call starts.
+int order_after(es_handle* h, hipStream_t to, hipStream_t from, hipEvent_t ev)
+{
+    if (to == from) return ES_OK;
+    ES_HIP(h, hipEventRecord(ev, from));
+    ES_HIP(h, hipStreamWaitEvent(to, ev, 0));
+    return ES_OK;
+}
+
+int sync_all(es_handle* h)
+{
+    ES_HIP(h, hipStreamSynchronize(h->s_main));
+    if (h->s_ctx != h->s_main) ES_HIP(h, hipStreamSynchronize(h->s_ctx));
+    if (h->s_stage != h->s_main && h->s_stage != h->s_ctx) ES_HIP(h, hipStreamSynchronize(h->s_stage));
+    h->stage_pending = false;
+    return ES_OK;
+}
+
+int check_ctx_call(es_handle* h, uint32_t est)
+{
+    if (!h || est >= h->N) return ES_EINVAL;
+    if (h->seg_bytes.empty()) return ES_OK;
+    if (!h->workers[h->worker_of[est]].bound) return ES_ESTATE;
+    return ES_OK;
+}
+
+int aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+
+}  // namespace
+
+extern "C" {
+
+int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
+{
+    if (!out || !lay || n_logical == 0 || n_logical > 65535) return ES_EINVAL;
+    if (lay->chunk_align == 0 || (lay->n_buckets && !lay->buckets)) return ES_EINVAL;
+    if (lay->n_state_segs && !lay->state_seg_bytes) return ES_EINVAL;
+    uint64_t pos = 0;
+    for (uint32_t b = 0; b < lay->n_buckets; ++b) {
+        if (lay->buckets[b].offset_elems != pos) return ES_EINVAL;        // ascending, disjoint, no gaps
+        if (lay->buckets[b].len_elems > (1ull << 40)) return ES_EINVAL;
+        pos += lay->buckets[b].len_elems;
+    }
+    if (pos != lay->n_params) return ES_EINVAL;
+    for (uint32_t j = 0; j < lay->n_state_segs; ++j)
+        if (lay->state_seg_bytes[j] == 0 || lay->state_seg_bytes[j] > (1ull << 32)) return ES_EINVAL;
+
+    es_handle* h = new (std::nothrow) es_handle;
+    if (!h) return ES_ENOMEM;
+    int rc = ES_OK;
+    try {
+        h->N = n_logical;
+        h->P = lay->n_params;
+        h->A = lay->chunk_align;
+        h->buckets.assign(lay->buckets, lay->buckets + lay->n_buckets);
+        uint64_t off = 0;
+        for (uint32_t j = 0; j < lay->n_state_segs; ++j) {
+            h->seg_bytes.push_back(lay->state_seg_bytes[j]);
+            h->seg_off.push_back(off);
+            off += round_up(lay->state_seg_bytes[j], 16);
+        }
+        h->ctx_bytes = off;
+        h->ctx_stride = round_up(off, kSlotAlignBytes);
+        h->grad_stride = round_up(h->P * sizeof(float), kSlotAlignBytes) / sizeof(float);
+        h->worker_of.assign(h->N, 0);
+        h->slot_of.resize(h->N);
+        for (uint32_t e = 0; e < h->N; ++e) h->slot_of[e] = e;
+        h->accumulated.assign((size_t)h->N * h->buckets.size(), 0);
+        h->workers.resize(1);
+        h->workers[0].live.assign(h->seg_bytes.size(), nullptr);
+    } catch (const std::bad_alloc&) {
+        delete h;
+        return ES_ENOMEM;
+    }
+    hipError_t e = hipGetDevice(&h->device);
+    if (e != hipSuccess) { delete h; return ES_EHIP; }
+    if ((e = hipEventCreateWithFlags(&h->ev_main, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&h->ev_ctx, hipEventDisableTiming)) != hipSuccess ||
+        (e = hipEventCreateWithFlags(&h->ev_stage, hipEventDisableTiming)) != hipSuccess) {
+        es_destroy(h);
+        return ES_EHIP;
+    }
+    rc = alloc_worker(h, h->workers[0], h->N);
+    if (rc == ES_OK) rc = build_tiles(h);
+    if (rc == ES_OK) rc = upload_slot_table(h);
+    if (rc != ES_OK) { es_destroy(h); return rc; }
+    *out = h;
+    return ES_OK;
+}
+
+int es_destroy(es_handle* h)
+{
+    if (!h) return ES_EINVAL;
+    (void)hipStreamSynchronize(h->s_main);
+    (void)hipStreamSynchronize(h->s_ctx);
+    (void)hipStreamSynchronize(h->s_stage);
+    for (Worker& w : h->workers) free_worker(w);
+    if (h->d_tiles) (void)hipFree(h->d_tiles);
+    if (h->d_slots) (void)hipFree((void*)h->d_slots);
+    if (h->ev_main) (void)hipEventDestroy(h->ev_main);
+    if (h->ev_ctx) (void)hipEventDestroy(h->ev_ctx);
+    if (h->ev_stage) (void)hipEventDestroy(h->ev_stage);
+    delete h;
+    return ES_OK;
+}
+
+int es_set_streams(es_handle* h, void* main, void* ctx, void* stage)
+{
+    if (!h) return ES_EINVAL;
+    int rc = sync_all(h);
+    if (rc != ES_OK) return rc;
+    h->s_main = (hipStream_t)main;
+    h->s_ctx = (hipStream_t)ctx;
+    h->s_stage = (hipStream_t)stage;
+    return ES_OK;
+}
+
+int es_set_grouping(es_handle* h, uint32_t n_workers, const uint32_t* worker_of_est,
+                    const uint32_t* slot_of_est)
+{
+    if (!h || !worker_of_est || !slot_of_est) return ES_EINVAL;
+    std::vector<uint32_t> counts;
+    if (!valid_grouping(h->N, n_workers, worker_of_est, slot_of_est, counts)) return ES_EINVAL;
+    if (h->n_accumulated != 0) return ES_ESTATE;
+    int rc = sync_all(h);
+    if (rc != ES_OK) return rc;
+
+    std::vector<Worker> fresh(n_workers);
+    for (uint32_t w = 0; w < n_workers && rc == ES_OK; ++w) {
+        fresh[w].live.assign(h->seg_bytes.size(), nullptr);
+        rc = alloc_worker(h, fresh[w], counts[w]);
+    }
+    // carry every EST's small-state context over to its new slot
+    if (rc == ES_OK && h->ctx_bytes) {
+        for (uint32_t e = 0; e < h->N && rc == ES_OK; ++e) {
+            uint8_t* dst = fresh[worker_of_est[e]].ctx_arena + (uint64_t)slot_of_est[e] * h->ctx_stride;
+            hipError_t he = launch_copy_bytes(h->s_main, dst, ctx_base(h, e), h->ctx_bytes);
+            if (he != hipSuccess) rc = hip_fail(h, he);
+        }
+        if (rc == ES_OK) {
+            hipError_t he = hipStreamSynchronize(h->s_main);
+            if (he != hipSuccess) rc = hip_fail(h, he);
+        }
+    }
+    if (rc != ES_OK) {
+        for (Worker& w : fresh) free_worker(w);
+        return rc;
+    }
+    for (Worker& w : h->workers) free_worker(w);
+    h->workers.swap(fresh);
+    h->worker_of.assign(worker_of_est, worker_of_est + h->N);
+    h->slot_of.assign(slot_of_est, slot_of_est + h->N);
+    return upload_slot_table(h);
+}
+
+int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs)
+{
+    if (!h || worker >= h->workers.size()) return ES_EINVAL;
+    const size_t ns = h->seg_bytes.size();
+    if (ns && !live_ptrs) return ES_EINVAL;
+    for (size_t j = 0; j < ns; ++j)
+        if (!live_ptrs[j]) return ES_EINVAL;
+    for (size_t j = 0; j < ns; ++j)                      // live tensors must not overlap
+        for (size_t k = j + 1; k < ns; ++k) {
+            const uintptr_t a = (uintptr_t)live_ptrs[j], b = (uintptr_t)live_ptrs[k];
+            if (a < b + h->seg_bytes[k] && b < a + h->seg_bytes[j]) return ES_EINVAL;
+        }
+    int rc = sync_all(h);
+    if (rc != ES_OK) return rc;
+    Worker& w = h->workers[worker];
+    std::vector<Piece> pieces;
+    for (size_t j = 0; j < ns; ++j) {
+        const uintptr_t p = (uintptr_t)live_ptrs[j];
+        const uint64_t nb = h->seg_bytes[j];
+        const uint32_t width = ((p | nb) & 15) == 0 ? 16 : ((p | nb) & 3) == 0 ? 4 : 1;
+        for (uint64_t o = 0; o < nb; o += kPieceBytes) {
+            Piece pc;
+            pc.live = (void*)(p + o);
+            pc.slot_off = h->seg_off[j] + o;
+            pc.nbytes = (uint32_t)std::min<uint64_t>(kPieceBytes, nb - o);
+            pc.width = width;
+            pieces.push_back(pc);
+        }
+    }
+    if (w.d_pieces) { (void)hipFree(w.d_pieces); w.d_pieces = nullptr; }
+    w.n_pieces = (uint32_t)pieces.size();
+    if (w.n_pieces) {
+        ES_HIP(h, hipMalloc((void**)&w.d_pieces, pieces.size() * sizeof(Piece)));
+        ES_HIP(h, hipMemcpy(w.d_pieces, pieces.data(), pieces.size() * sizeof(Piece), hipMemcpyHostToDevice));
+    }
+    w.live.assign(live_ptrs, live_ptrs + ns);
+    w.bound = true;
+    return ES_OK;
+}
+
+int es_ctx_restore(es_handle* h, uint32_t est)
+{
+    int rc = check_ctx_call(h, est);
+    if (rc != ES_OK) return rc;
+    if (h->seg_bytes.empty()) return ES_OK;
+    const Worker& w = h->workers[h->worker_of[est]];
+    if ((rc = order_after(h, h->s_ctx, h->s_main, h->ev_main)) != ES_OK) return rc;
+    ES_HIP(h, launch_ctx(h->s_ctx, w.d_pieces, w.n_pieces, ctx_base(h, est), nullptr, kRestore));
+    return order_after(h, h->s_main, h->s_ctx, h->ev_ctx);
+}
+
+int es_ctx_save(es_handle* h, uint32_t est)
+{
+    int rc = check_ctx_call(h, est);
+    if (rc != ES_OK) return rc;
+    if (h->seg_bytes.empty()) return ES_OK;
+    const Worker& w = h->workers[h->worker_of[est]];
+    if ((rc = order_after(h, h->s_ctx, h->s_main, h->ev_main)) != ES_OK) return rc;
+    ES_HIP(h, launch_ctx(h->s_ctx, w.d_pieces, w.n_pieces, ctx_base(h, est), nullptr, kSave));
+    return ES_OK;
+}
+
+int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in)
+{
+    if (!h || est_out >= h->N || est_in >= h->N || est_out == est_in) return ES_EINVAL;
+    if (h->worker_of[est_out] != h->worker_of[est_in]) return ES_EINVAL;
+    if (h->seg_bytes.empty()) return ES_OK;
+    const Worker& w = h->workers[h->worker_of[est_out]];
+    if (!w.bound) return ES_ESTATE;
+    int rc = order_after(h, h->s_ctx, h->s_main, h->ev_main);
+    if (rc != ES_OK) return rc;
+    ES_HIP(h, launch_ctx(h->s_ctx, w.d_pieces, w.n_pieces, ctx_base(h, est_out), ctx_base(h, est_in), kSwitch));
+    return order_after(h, h->s_main, h->s_ctx, h->ev_ctx);
+}
+
+float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket)
+{
+    if (!h || est >= h->N || bucket >= h->buckets.size()) return nullptr;
+    return slot_base(h, est) + h->buckets[bucket].offset_elems;
+}
+
+int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_grad_bucket)
+{
+    if (!h || est >= h->N || bucket >= h->buckets.size()) return ES_EINVAL;
+    const uint64_t len = h->buckets[bucket].len_elems;
+    if (len && (!d_grad_bucket || (((uintptr_t)d_grad_bucket) & 3))) return ES_EINVAL;
+    uint8_t& flag = h->accumulated[(size_t)est * h->buckets.size() + bucket];
+    if (flag) return ES_ESTATE;
+    float* dst = es_grad_slot(h, est, bucket);
+    if (len && d_grad_bucket != dst) {
+        // a source that overlaps the destination slot without being it cannot be copied in one pass
+        const uintptr_t a = (uintptr_t)d_grad_bucket, b = (uintptr_t)dst, n = len * sizeof(float);
+        if (a < b + n && b < a + n) return ES_EINVAL;
+        int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
+        if (rc != ES_OK) return rc;
+        ES_HIP(h, launch_copy_f32(h->s_stage, dst, d_grad_bucket, len));
+        h->stage_pending = true;
+    }
+    flag = 1;
+    h->n_accumulated++;
+    return ES_OK;
+}
+
+int es_stage_fence(es_handle* h)
+{
+    if (!h) return ES_EINVAL;
+    if (!h->stage_pending) return ES_OK;
+    int rc = order_after(h, h->s_main, h->s_stage, h->ev_stage);
+    if (rc == ES_OK) h->stage_pending = false;
+    return rc;
+}
+
+int es_dropout_mask(es_handle* h, uint32_t est, uint32_t state_seg, uint8_t* d_mask, uint64_t n,
+                    double p)
+{
+    if (!h || est >= h->N || state_seg >= h->seg_bytes.size()) return ES_EINVAL;
+    if (h->seg_bytes[state_seg] != 16 || (n && !d_mask) || !(p >= 0.0 && p <= 1.0)) return ES_EINVAL;
+    const Worker& w = h->workers[h->worker_of[est]];
+    if (!w.bound) return ES_ESTATE;
+    if (((uintptr_t)w.live[state_seg]) & 7) return ES_EINVAL;
+    uint64_t thr = p >= 1.0 ? (1ull << 32) : (uint64_t)(p * 4294967296.0);
+    ES_HIP(h, launch_dropout_mask(h->s_main, (uint64_t*)w.live[state_seg], d_mask, n, thr));
+    return ES_OK;
+}
+
+static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr, float mu)
+{
+    if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
+    int rc = es_stage_fence(h);
+    if (rc != ES_OK) return rc;
+    ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));
+    std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
+    h->n_accumulated = 0;
+    return ES_OK;
+}
+
+int es_ring_order_reduce(es_handle* h, float* d_avg_grad)
+{
+    if (!h || (h->P && (!d_avg_grad || !aligned16(d_avg_grad)))) return ES_EINVAL;
+    return reduce_common(h, d_avg_grad, nullptr, nullptr, 0.f, 0.f);
+}
+
+int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_avg_grad,
+                float lr, float mu)
+{
+    if (!h) return ES_EINVAL;
+    if (h->P && (!d_param || !d_momentum || !d_avg_grad)) return ES_EINVAL;
+    if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
+    ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu));
+    return ES_OK;
+}
+
+int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum, float* d_avg_grad,
+                       float lr, float mu)
+{
+    if (!h) return ES_EINVAL;
+    if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
+    if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
+    return reduce_common(h, d_avg_grad, d_param, d_momentum, lr, mu);
+}
+
+int es_sync(es_handle* h)
+{
+    if (!h) return ES_EINVAL;
+    return sync_all(h);
+}
+
+int es_set_option(es_handle* h, const char* name, int64_t value)
+{
+    if (!h || !name) return ES_EINVAL;
+    const std::string k(name);
+    if (k == "reduce_tile_elems") {
+        if (value < 256 || value > 65536 || (value & 3)) return ES_EINVAL;
+        int rc = sync_all(h);
+        if (rc != ES_OK) return rc;
+        const uint32_t old = h->tile_elems;
+        h->tile_elems = (uint32_t)value;
+        rc = build_tiles(h);
+        if (rc != ES_OK) { h->tile_elems = old; (void)build_tiles(h); }
+        return rc;
+    }
+    if (k == "reduce_unroll") {
+        if (value != 1 && value != 2 && value != 4) return ES_EINVAL;
+        h->shape.unroll = (int)value;
+        return ES_OK;
+    }
+    if (k == "reduce_rank_batch") {
+        if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return ES_EINVAL;
+        h->shape.rank_batch = (int)value;
+        return ES_OK;
+    }
+    if (k == "nontemporal") {
+        if (value != 0 && value != 1) return ES_EINVAL;
+        h->shape.nontemporal = (int)value;
+        return ES_OK;
+    }
+    return ES_EINVAL;
+}
+
+int es_get_option(es_handle* h, const char* name, int64_t* value)
+{
+    if (!h || !name || !value) return ES_EINVAL;
+    const std::string k(name);
+    if (k == "reduce_tile_elems") *value = h->tile_elems;
+    else if (k == "reduce_unroll") *value = h->shape.unroll;
+    else if (k == "reduce_rank_batch") *value = h->shape.rank_batch;
+    else if (k == "nontemporal") *value = h->shape.nontemporal;
+    else return ES_EINVAL;
+    return ES_OK;
+}
+
+int es_query(es_handle* h, uint64_t* n_params, uint32_t* n_buckets, uint64_t* ctx_bytes,
+             uint32_t* n_workers, uint64_t* n_reduce_tiles)
+{
+    if (!h) return ES_EINVAL;
+    if (n_params) *n_params = h->P;
+    if (n_buckets) *n_buckets = (uint32_t)h->buckets.size();
+    if (ctx_bytes) *ctx_bytes = h->ctx_bytes;
+    if (n_workers) *n_workers = (uint32_t)h->workers.size();
+    if (n_reduce_tiles) *n_reduce_tiles = h->n_tiles;
+    return ES_OK;
+}
+
+int es_last_hip_error(es_handle* h) { return h ? h->last_hip : 0; }
+
+const char* es_strerror(int status)
+{
+    switch (status) {
+    case ES_OK:     return "ok";
+    case ES_EINVAL: return "invalid argument";
+    case ES_ESTATE: return "call not valid in the current state";
+    case ES_ENOMEM: return "out of memory";
+    case ES_EHIP:   return "HIP call failed";
+    default:        return "unknown status";
+    }
+}
+
+const char* es_version(void) { return "libes 0.1 (gfx950)"; }
+
+}  // extern "C"

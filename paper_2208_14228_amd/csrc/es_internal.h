@@ -1,0 +1,63 @@
+// Internal interface between the host runtime (es_api.cpp) and the gfx950
+// kernels (es_kernels.hip).  Not part of the public boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace es {
+
+// One workgroup's share of the ring-ordered reduction: a contiguous range of
+// the flat parameter space that lies inside a single ring chunk, so the rank
+// the fold starts at is the same for every element of the tile.
+struct Tile {
+    uint64_t off;      // first element (flat parameter space)
+    uint32_t len;      // elements
+    uint32_t rank0;    // virtual rank whose gradient opens the fold (= chunk index)
+};
+static_assert(sizeof(Tile) == 16, "Tile is read with one 16-byte scalar load");
+
+// One workgroup's share of a small-state context copy.
+struct Piece {
+    void*    live;       // device address inside a live state tensor
+    uint64_t slot_off;   // byte offset inside the EST's context slot
+    uint32_t nbytes;     // <= kPieceBytes
+    uint32_t width;      // 16, 4 or 1: widest access both sides are aligned for
+};
+static_assert(sizeof(Piece) == 24, "Piece layout");
+
+constexpr uint32_t kPieceBytes = 4096;
+constexpr uint32_t kBlock = 256;
+
+struct ReduceShape {
+    int unroll;        // 16-byte vectors per lane per rank
+    int rank_batch;    // ranks loaded before adds are issued
+    int nontemporal;   // streaming hint on gradient loads
+};
+
+// ring-ordered N-way reduce (+ optional fused SGD-momentum).
+//  slots: device table of N slot base pointers indexed by virtual rank.
+//  avg may be null only when p and v are given.
+hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+                              const float* const* slots, uint32_t N,
+                              float* avg, float* p, float* v, float lr, float mu,
+                              ReduceShape shape);
+
+hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
+                      float lr, float mu);
+
+// dst[0..n) <- src[0..n) floats (any 4-byte alignment)
+hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n);
+
+enum CtxDir { kSave = 0, kRestore = 1, kSwitch = 2 };
+// kSave:    slot_a <- live;  kRestore: live <- slot_a;
+// kSwitch:  slot_a <- live, then live <- slot_b (per byte, same lane)
+hipError_t launch_ctx(hipStream_t s, const Piece* pieces, uint32_t n_pieces,
+                      uint8_t* slot_a, const uint8_t* slot_b, CtxDir dir);
+
+// generic byte copy used when contexts move between arenas
+hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, uint64_t n);
+
+hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, uint64_t n,
+                               uint64_t threshold);
+
+}  // namespace es

@@ -1,0 +1,479 @@
+// gfx950 (CDNA4) kernels of the EST step.  Wave size 64, 256-lane workgroups.
+//
+// Bit-exactness rules that hold for every kernel in this file:
+//  - fp32 IEEE arithmetic, denormals kept, no fused multiply-add (the file is
+//    compiled with -ffp-contract=off), division correctly rounded;
+//  - no atomics; no arithmetic across lanes: a sum over N ranks is a chain of
+//    N-1 adds in one lane in program order, so neither the grid shape nor the
+//    order in which loads return can change a bit;
+//  - loads may be issued early and in any order, only the add chain is ordered.
+#include "es_internal.h"
+
+namespace es {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+// Tables that every lane of a workgroup reads at the same index live in the
+// constant address space so the reads are scalar loads shared by the wave.
+#define ES_CONST_AS __attribute__((address_space(4)))
+#pragma clang diagnostic ignored "-Wold-style-cast"
+
+template <bool NT>
+__device__ __forceinline__ f4 ld4(const float* p)
+{
+    const f4* q = reinterpret_cast<const f4*>(p);
+    if constexpr (NT)
+        return __builtin_nontemporal_load(q);
+    else
+        return *q;
+}
+
+__device__ __forceinline__ void st4(float* p, f4 x) { *reinterpret_cast<f4*>(p) = x; }
+
+// ---------------------------------------------------------------------------
+// Ring-ordered N-way reduce (paper §3.3 D1: aggregation order fixed by the
+// ESTs' constant virtual ranks), optionally fused with the SGD-momentum update
+// of the shared replica (paper §3.2).
+//
+// One workgroup = one Tile (a range inside one ring chunk).  Chunk c's sum is
+// the left fold over ranks c, c+1, ..., c+N-1 (mod N): what the reduce-scatter
+// of an N-rank ring computes when rank r sends to r+1 and first sends its own
+// chunk.  Each lane keeps U independent 16-byte accumulators and loads NB ranks
+// ahead of the adds.
+// ---------------------------------------------------------------------------
+template <int U, int NB, bool NT, bool FIRST>
+__device__ __forceinline__ void fold_batch(const float* const ES_CONST_AS* slots, uint32_t N,
+                                           uint32_t r0, const uint64_t (&e)[U], f4 (&acc)[U])
+{
+    // ranks r0 .. r0+NB-1 (mod N): all loads first, then the adds in rank order
+    f4 x[NB][U];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        uint32_t r = r0 + j;
+        if (r >= N) r -= N;
+        const float* g = slots[r];
+#pragma unroll
+        for (int u = 0; u < U; ++u) x[j][u] = ld4<NT>(g + e[u]);
+    }
+    // keep every load of the batch ahead of the first add: the batch is the
+    // wave's bytes in flight
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (FIRST && j == 0)
+                acc[u] = x[0][u];                          // the fold opens with rank c itself
+            else
+                acc[u] = acc[u] + x[j][u];
+        }
+    }
+}
+
+template <bool SGD>
+__device__ __forceinline__ void finish_scalar(float acc, float fN, uint64_t e, float* avg,
+                                              float* p, float* v, float lr, float mu)
+{
+    const float a = acc / fN;
+    if (avg) avg[e] = a;
+    if constexpr (SGD) {
+        const float mv = mu * v[e];
+        const float vn = mv + a;
+        const float st = lr * vn;
+        v[e] = vn;
+        p[e] = p[e] - st;
+    }
+}
+
+template <bool SGD>
+__device__ __forceinline__ void fold_scalar(const float* const ES_CONST_AS* slots, uint32_t N,
+                                            uint32_t rank0, float fN, uint64_t e, float* avg,
+                                            float* p, float* v, float lr, float mu)
+{
+    uint32_t r = rank0;
+    float acc = slots[r][e];
+    for (uint32_t k = 1; k < N; ++k) {
+        r = (r + 1 == N) ? 0 : r + 1;
+        acc = acc + slots[r][e];
+    }
+    finish_scalar<SGD>(acc, fN, e, avg, p, v, lr, mu);
+}
+
+template <int U, int NB, bool NT, bool SGD>
+__global__ __launch_bounds__(kBlock) void k_ring_reduce(const Tile* tiles_g,
+                                                        const float* const* slots_g, uint32_t N,
+                                                        float* __restrict__ avg,
+                                                        float* __restrict__ p,
+                                                        float* __restrict__ v, float lr, float mu)
+{
+    const Tile ES_CONST_AS* tiles = (const Tile ES_CONST_AS*)tiles_g;
+    const float* const ES_CONST_AS* slots = (const float* const ES_CONST_AS*)slots_g;
+
+    const uint64_t off = tiles[blockIdx.x].off;
+    const uint32_t len = tiles[blockIdx.x].len;
+    const uint32_t rank0 = tiles[blockIdx.x].rank0;
+    const float fN = (float)N;
+
+    // 16-byte vectors need element offsets that are multiples of 4 (all slot,
+    // avg, p and v bases are 16-byte aligned): up to 3 leading and 3 trailing
+    // elements of a tile take the scalar path.
+    uint32_t head = (uint32_t)((4 - (off & 3)) & 3);
+    if (head > len) head = len;
+    const uint32_t nvec = (len - head) >> 2;
+    const uint64_t vbase = off + head;
+    const uint32_t tail = len - head - 4 * nvec;
+
+    for (uint32_t i0 = threadIdx.x; i0 < nvec; i0 += kBlock * U) {
+        uint64_t e[U];
+        bool ok[U];
+        f4 acc[U], pp[U], vv[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t i = i0 + u * kBlock;
+            ok[u] = i < nvec;
+            // a lane without work in this pass re-reads the tile's last vector
+            // (in bounds, result dropped) so that no load needs a predicate
+            e[u] = vbase + 4ull * (ok[u] ? i : nvec - 1);
+        }
+        if constexpr (SGD) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                pp[u] = ld4<false>(p + e[u]);
+                vv[u] = ld4<false>(v + e[u]);
+            }
+        }
+        // N = q*NB + rem ranks: q full batches, then the rest one rank at a time
+        uint32_t k;
+        if (N >= (uint32_t)NB) {
+            fold_batch<U, NB, NT, true>(slots, N, rank0, e, acc);
+            k = NB;
+        } else {
+            fold_batch<U, 1, NT, true>(slots, N, rank0, e, acc);
+            k = 1;
+        }
+        for (; k + NB <= N; k += NB) {
+            uint32_t r0 = rank0 + k;
+            if (r0 >= N) r0 -= N;
+            fold_batch<U, NB, NT, false>(slots, N, r0, e, acc);
+        }
+        for (; k < N; ++k) {
+            uint32_t r0 = rank0 + k;
+            if (r0 >= N) r0 -= N;
+            fold_batch<U, 1, NT, false>(slots, N, r0, e, acc);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            const f4 a = acc[u] / fN;
+            if (avg) st4(avg + e[u], a);
+            if constexpr (SGD) {
+                const f4 mv = mu * vv[u];
+                const f4 vn = mv + a;
+                const f4 st = lr * vn;
+                st4(v + e[u], vn);
+                st4(p + e[u], pp[u] - st);
+            }
+        }
+    }
+    if (threadIdx.x < head)
+        fold_scalar<SGD>(slots, N, rank0, fN, off + threadIdx.x, avg, p, v, lr, mu);
+    if (threadIdx.x < tail)
+        fold_scalar<SGD>(slots, N, rank0, fN, vbase + 4ull * nvec + threadIdx.x, avg, p, v, lr, mu);
+}
+
+template <int U, int NB>
+static hipError_t launch_reduce_unb(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+                                    const float* const* slots, uint32_t N, float* avg, float* p,
+                                    float* v, float lr, float mu, bool nt)
+{
+    const bool sgd = p != nullptr;
+    dim3 grid(n_tiles), block(kBlock);
+    if (nt) {
+        if (sgd) hipLaunchKernelGGL((k_ring_reduce<U, NB, true, true>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu);
+        else     hipLaunchKernelGGL((k_ring_reduce<U, NB, true, false>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu);
+    } else {
+        if (sgd) hipLaunchKernelGGL((k_ring_reduce<U, NB, false, true>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu);
+        else     hipLaunchKernelGGL((k_ring_reduce<U, NB, false, false>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu);
+    }
+    return hipGetLastError();
+}
+
+template <int U>
+static hipError_t launch_reduce_u(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+                                  const float* const* slots, uint32_t N, float* avg, float* p,
+                                  float* v, float lr, float mu, ReduceShape sh)
+{
+    const bool nt = sh.nontemporal != 0;
+    switch (sh.rank_batch) {
+    case 1:  return launch_reduce_unb<U, 1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    case 2:  return launch_reduce_unb<U, 2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    case 4:  return launch_reduce_unb<U, 4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    case 8:  return launch_reduce_unb<U, 8>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    case 16: return launch_reduce_unb<U, 16>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+                              const float* const* slots, uint32_t N, float* avg, float* p,
+                              float* v, float lr, float mu, ReduceShape sh)
+{
+    if (n_tiles == 0) return hipSuccess;
+    switch (sh.unroll) {
+    case 1: return launch_reduce_u<1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, sh);
+    case 2: return launch_reduce_u<2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, sh);
+    case 4: return launch_reduce_u<4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, sh);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// SGD with momentum on the shared replica (paper §3.2), unfused form.
+// ---------------------------------------------------------------------------
+constexpr int kSgdU = 4;
+
+__global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ p, float* __restrict__ v,
+                                                const float* __restrict__ g, uint64_t n,
+                                                float lr, float mu)
+{
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * kSgdU) + threadIdx.x;
+    f4 pp[kSgdU], vv[kSgdU], gg[kSgdU];
+#pragma unroll
+    for (int u = 0; u < kSgdU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) {
+            gg[u] = ld4<true>(g + 4 * i);
+            pp[u] = ld4<false>(p + 4 * i);
+            vv[u] = ld4<false>(v + 4 * i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kSgdU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) {
+            const f4 mv = mu * vv[u];
+            const f4 vn = mv + gg[u];
+            const f4 st = lr * vn;
+            st4(v + 4 * i, vn);
+            st4(p + 4 * i, pp[u] - st);
+        }
+    }
+    if (blockIdx.x == 0) {
+        const uint64_t e = 4 * nvec + threadIdx.x;
+        if (e < n) {
+            const float mv = mu * v[e];
+            const float vn = mv + g[e];
+            const float st = lr * vn;
+            v[e] = vn;
+            p[e] = p[e] - st;
+        }
+    }
+}
+
+hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_t n, float lr,
+                      float mu)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t nvec = n >> 2;
+    uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(k_sgd, dim3((uint32_t)blocks), dim3(kBlock), 0, s, p, v, g, n, lr, mu);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Gradient staging: copy one bucket into an EST's context slot (paper §3.2).
+// ---------------------------------------------------------------------------
+constexpr int kCopyU = 4;
+
+__global__ __launch_bounds__(kBlock) void k_copy_f4(float* __restrict__ dst,
+                                                    const float* __restrict__ src, uint64_t n)
+{
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * kCopyU) + threadIdx.x;
+    f4 x[kCopyU];
+#pragma unroll
+    for (int u = 0; u < kCopyU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) x[u] = ld4<true>(src + 4 * i);
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) st4(dst + 4 * i, x[u]);
+    }
+    if (blockIdx.x == 0) {
+        const uint64_t e = 4 * nvec + threadIdx.x;
+        if (e < n) dst[e] = src[e];
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_copy_f1(float* __restrict__ dst,
+                                                    const float* __restrict__ src, uint64_t n)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) dst[i] = src[i];
+}
+
+hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n)
+{
+    if (n == 0) return hipSuccess;
+    if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
+        uint64_t blocks = ((n >> 2) + kBlock * kCopyU - 1) / (kBlock * kCopyU);
+        if (blocks == 0) blocks = 1;
+        hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
+    } else {
+        const uint64_t blocks = (n + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(k_copy_f1, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
+    }
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(kBlock) void k_copy_bytes(uint8_t* __restrict__ dst,
+                                                       const uint8_t* __restrict__ src, uint64_t n16)
+{
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n16) reinterpret_cast<u4*>(dst)[i] = reinterpret_cast<const u4*>(src)[i];
+}
+
+// dst, src 16-byte aligned, n a multiple of 16
+hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, uint64_t n)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t n16 = n >> 4;
+    const uint64_t blocks = (n16 + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(k_copy_bytes, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n16);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Small-state context switch (paper §3.2): scattered live tensors <-> one
+// contiguous slot, all segments in one launch.  One workgroup per Piece.
+// In kSwitch every lane reads its live bytes, then overwrites them with the
+// incoming EST's bytes: outgoing and incoming state never meet across lanes.
+// ---------------------------------------------------------------------------
+template <typename T>
+__device__ __forceinline__ void ctx_move(T* live, T* sa, const T* sb, uint32_t n, int dir)
+{
+    for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
+        if (dir == kSave) {
+            sa[i] = live[i];
+        } else if (dir == kRestore) {
+            live[i] = sa[i];
+        } else {
+            const T out = live[i];
+            const T in = sb[i];
+            sa[i] = out;
+            live[i] = in;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_ctx(const Piece* pieces_g, uint8_t* slot_a,
+                                                const uint8_t* slot_b, int dir)
+{
+    const Piece ES_CONST_AS* pieces = (const Piece ES_CONST_AS*)pieces_g;
+    uint8_t* live = (uint8_t*)pieces[blockIdx.x].live;
+    const uint64_t so = pieces[blockIdx.x].slot_off;
+    const uint32_t nb = pieces[blockIdx.x].nbytes;
+    const uint32_t w = pieces[blockIdx.x].width;
+    uint8_t* sa = slot_a + so;
+    const uint8_t* sb = slot_b ? slot_b + so : nullptr;
+    if (w == 16)
+        ctx_move<u4>((u4*)live, (u4*)sa, (const u4*)sb, nb >> 4, dir);
+    else if (w == 4)
+        ctx_move<uint32_t>((uint32_t*)live, (uint32_t*)sa, (const uint32_t*)sb, nb >> 2, dir);
+    else
+        ctx_move<uint8_t>(live, sa, sb, nb, dir);
+}
+
+hipError_t launch_ctx(hipStream_t s, const Piece* pieces, uint32_t n_pieces, uint8_t* slot_a,
+                      const uint8_t* slot_b, CtxDir dir)
+{
+    if (n_pieces == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_ctx, dim3(n_pieces), dim3(kBlock), 0, s, pieces, slot_a, slot_b, (int)dir);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Dropout keep-mask from an EST's live RNG state (paper §3.3: Dropout depends
+// on RNG state, which is therefore EST context).  Philox4x32-10 after Salmon,
+// Moraes, Dror, Shaw (SC'11): ten rounds of two 32x32->64 multiplies whose
+// high halves are mixed with the other two counter words and the key; the key
+// advances by two Weyl constants per round.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t a = (uint64_t)0xD2511F53u * c0;
+        const uint64_t b = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(b >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(a >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)b;
+        c3 = (uint32_t)a;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// Each lane draws 4 counter values = 16 mask bytes.
+__global__ __launch_bounds__(kBlock) void k_dropout_mask(const uint64_t* __restrict__ state,
+                                                         uint8_t* __restrict__ mask, uint64_t n,
+                                                         uint64_t threshold, int aligned16)
+{
+    const uint64_t seed = state[0];
+    const uint64_t offset = state[1];
+    const uint64_t t = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t j0 = 16 * t;
+    if (j0 >= n) return;
+    const uint32_t k0 = (uint32_t)seed, k1 = (uint32_t)(seed >> 32);
+    uint32_t packed[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint64_t pos = offset + 4 * t + q;
+        uint32_t w[4];
+        philox4x32_10((uint32_t)pos, (uint32_t)(pos >> 32), 0u, 0u, k0, k1, w);
+        uint32_t word = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            word |= ((uint64_t)w[k] >= threshold ? 1u : 0u) << (8 * k);
+        packed[q] = word;
+    }
+    if (aligned16 && j0 + 16 <= n) {
+        u4 o = {packed[0], packed[1], packed[2], packed[3]};
+        *reinterpret_cast<u4*>(mask + j0) = o;
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (j0 + i < n) mask[j0 + i] = (uint8_t)((packed[i >> 2] >> (8 * (i & 3))) & 0xFF);
+    }
+}
+
+__global__ void k_philox_advance(uint64_t* state, uint64_t blocks)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) state[1] = state[1] + blocks;
+}
+
+hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, uint64_t n,
+                               uint64_t threshold)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t lanes = (n + 15) / 16;
+    const uint64_t blocks = (lanes + kBlock - 1) / kBlock;
+    const int aligned16 = (((uintptr_t)mask) & 15) == 0;
+    hipLaunchKernelGGL(k_dropout_mask, dim3((uint32_t)blocks), dim3(kBlock), 0, s, state, mask, n,
+                       threshold, aligned16);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_philox_advance, dim3(1), dim3(64), 0, s, state, (n + 3) / 4);
+    return hipGetLastError();
+}
+
+}  // namespace es

@@ -1,0 +1,166 @@
+"""Runs a tests/scenario.Scenario through the HIP library (C boundary via the
+ctypes binding) and collects the same Result the CPU references produce."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+import scenario as S
+from paper_2208_14228_amd import binding as B
+from paper_2208_14228_amd.job import ESTJob
+from workloads import synth
+from workloads.configs import Grouping
+
+DEV = "cuda:0"
+
+
+def seg_bytes(sc: S.Scenario) -> List[int]:
+    segs = [16] if sc.mask_n else []
+    segs += [4 * ln for _, ln in sc.bn_segments]
+    return segs
+
+
+def make_job(sc: S.Scenario, g: Grouping, use_streams=True, live_alloc=None, options=None) -> ESTJob:
+    job = ESTJob(sc.n_logical, sc.layout.n_params, sc.layout.buckets, sc.chunk_align, seg_bytes(sc),
+                 g.worker_of_est, g.slot_of_est, DEV, use_streams, live_alloc)
+    for k, v in (options or {}).items():
+        job.set_option(k, v)
+    return job
+
+
+def _bn_views(sc: S.Scenario, job: ESTJob, e: int) -> List[torch.Tensor]:
+    live = job.live_of(e)
+    return [t.view(torch.float32) if t.data_ptr() % 4 == 0 else t for t in live[(1 if sc.mask_n else 0):]]
+
+
+def write_live(sc: S.Scenario, job: ESTJob, e: int, philox: Optional[Tuple[int, int]],
+               bn: Optional[torch.Tensor]) -> None:
+    """Fill the live tensors of e's worker (torch copies on the job's main stream)."""
+    live = job.live_of(e)
+    with job.stream_ctx():
+        if sc.mask_n:
+            st = torch.tensor(np.array(philox, dtype=np.uint64).view(np.uint8), device=DEV)
+            live[0].copy_(st)
+        if sc.bn_len:
+            off0 = 1 if sc.mask_n else 0
+            raw = bn.contiguous().view(torch.uint8)
+            for j, (o, ln) in enumerate(sc.bn_segments):
+                live[off0 + j].copy_(raw[4 * o:4 * (o + ln)])
+
+
+def read_live(sc: S.Scenario, job: ESTJob, e: int):
+    live = job.live_of(e)
+    philox = bn = None
+    if sc.mask_n:
+        philox = live[0].cpu().numpy().view(np.uint64).copy()
+    if sc.bn_len:
+        off0 = 1 if sc.mask_n else 0
+        bn = np.concatenate([live[off0 + j].cpu().numpy().view(np.float32)
+                             for j in range(len(sc.bn_segments))])
+    return philox, bn
+
+
+def bn_add_live(sc: S.Scenario, job: ESTJob, e: int, delta: torch.Tensor) -> None:
+    """The mini-batch's effect on BatchNorm statistics: one fp32 add per element (torch, main stream)."""
+    live = job.live_of(e)
+    off0 = 1 if sc.mask_n else 0
+    with job.stream_ctx():
+        for j, (o, ln) in enumerate(sc.bn_segments):
+            t = live[off0 + j]
+            if t.data_ptr() % 4 == 0:
+                t.view(torch.float32).add_(delta[o:o + ln])
+            else:                       # unaligned live tensor: round-trip through an aligned copy
+                tmp = t.clone().view(torch.float32)
+                tmp.add_(delta[o:o + ln])
+                t.copy_(tmp.view(torch.uint8))
+
+
+def init_contexts(sc: S.Scenario, job: ESTJob) -> None:
+    for e in range(sc.n_logical):
+        write_live(sc, job, e, (S.philox_seed(sc, e), 0) if sc.mask_n else None,
+                   S.bn_init(sc, e, DEV) if sc.bn_len else None)
+        job.ctx_save(e)
+        job.sync()          # the next write to the live tensors must not overtake this save
+    with job.stream_ctx():
+        job.p.copy_(synth.params(sc.layout, sc.seed, DEV))
+        job.v.zero_()
+    job.sync()
+    torch.cuda.synchronize()
+
+
+def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=False,
+              sync_each_est=False, masks: Optional[Dict] = None, mask_check=None,
+              steps: Optional[Sequence[int]] = None) -> None:
+    mask = torch.empty(sc.mask_n, dtype=torch.uint8, device=DEV) if sc.mask_n else None
+    sched = g.schedule()
+    for t in (range(sc.steps) if steps is None else steps):
+        keep = []
+        for idx, e in enumerate(sched):
+            prev = sched[idx - 1] if idx else None
+            if (use_switch and prev is not None
+                    and g.worker_of_est[prev] == g.worker_of_est[e]):
+                job.ctx_switch(prev, e)
+            else:
+                if use_switch and prev is not None:
+                    job.ctx_save(prev)
+                job.ctx_restore(e)
+            if sc.mask_n:
+                job.dropout_mask(e, 0, mask, sc.p_drop)
+                job.sync()
+                if masks is not None:
+                    masks[(t, e)] = S.digest(mask.cpu().numpy())
+            if sc.bn_len:
+                bn_add_live(sc, job, e, S.bn_delta(sc, t, e, DEV))
+            with job.stream_ctx():
+                for b in range(sc.layout.n_buckets):
+                    gr = S.grad(sc, t, e, b, DEV)
+                    keep.append(gr)
+                    job.accumulate(e, b, gr)
+            if not use_switch:
+                job.ctx_save(e)
+            if sync_each_est:
+                job.sync()
+                torch.cuda.synchronize()
+                keep.clear()
+        if use_switch:
+            job.ctx_save(sched[-1])
+        if fused:
+            job.reduce_sgd_step(sc.lr, sc.momentum)
+        else:
+            job.ring_order_reduce()
+            job.sgd_step(sc.lr, sc.momentum)
+        job.sync()
+        torch.cuda.synchronize()
+        keep.clear()
+
+
+def collect(sc: S.Scenario, job: ESTJob, masks: Dict) -> S.Result:
+    philox, bn = [], []
+    for e in range(sc.n_logical):
+        if sc.mask_n or sc.bn_len:
+            job.ctx_restore(e)
+            job.sync()
+            torch.cuda.synchronize()
+            ph, b = read_live(sc, job, e)
+            philox.append(ph)
+            bn.append(b)
+    return S.Result(job.p.cpu().numpy(), job.v.cpu().numpy(), job.avg.cpu().numpy(),
+                    np.stack(philox) if sc.mask_n else None,
+                    np.stack(bn) if sc.bn_len else None, masks)
+
+
+def run_gpu(sc: S.Scenario, g: Grouping, fused=False, use_switch=False, use_streams=True,
+            options=None, live_alloc=None) -> S.Result:
+    print(f"[gpu-run] N={sc.n_logical} P={sc.layout.n_params} A={sc.chunk_align} seed={sc.seed:#x} "
+          f"grouping={g.name} fused={fused} switch={use_switch} streams={use_streams} opts={options}",
+          flush=True)
+    job = make_job(sc, g, use_streams, live_alloc, options)
+    try:
+        init_contexts(sc, job)
+        masks: Dict = {}
+        run_steps(sc, job, g, fused, use_switch, masks=masks)
+        return collect(sc, job, masks)
+    finally:
+        job.close()

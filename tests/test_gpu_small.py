@@ -1,0 +1,291 @@
+"""HIP path vs. CPU oracle, bit for bit, at sizes the oracle finishes in seconds:
+several tiles, ragged tails, empty buckets, every launch shape, every edge case."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import scenario as S
+from workloads import buckets, configs, synth
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import gpu_harness as G
+    from paper_2208_14228_amd import binding as B
+    from paper_2208_14228_amd.job import ESTJob
+
+
+def bits(a):
+    return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+
+
+def ragged_scenario(N, A, seed, **kw):
+    # bucket lengths: several tiles + ragged tail, empty, shorter than N, odd, exactly one tile
+    lay = buckets.custom([3 * 4096 + 37, 0, 3, 4096, 1001, 4 * N + 1, 20000 + N], fan_in=9)
+    return S.Scenario(N, lay, A, seed, **kw)
+
+
+@pytest.mark.parametrize("N,A", [(1, 1), (2, 4), (3, 1), (4, 4), (5, 4), (7, 1), (8, 4), (16, 4), (33, 1), (64, 4)])
+def test_ragged_parity_with_context(N, A):
+    sc = ragged_scenario(N, A, 100 + N, steps=2, mask_n=1003, bn_channels=(3, 64, 5))
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([N])
+    S.assert_same(G.run_gpu(sc, g), ref, f"N={N} unfused")
+    S.assert_same(G.run_gpu(sc, g, fused=True, use_streams=False), ref, f"N={N} fused")
+
+
+def test_every_launch_shape_gives_the_same_bits():
+    """Tile size, unroll, rank batch and the streaming hint are launch shape only."""
+    N = 12
+    sc = ragged_scenario(N, 4, 7, steps=1)
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([N])
+    job = G.make_job(sc, g)
+    try:
+        G.init_contexts(sc, job)
+        p0, v0 = job.p.clone(), job.v.clone()
+        for tile, u, nb, nt, fused in itertools.product((256, 1024, 4096, 16384), (1, 2, 4),
+                                                        (1, 2, 4, 8, 16), (0, 1), (False, True)):
+            for k, v in (("reduce_tile_elems", tile), ("reduce_unroll", u),
+                         ("reduce_rank_batch", nb), ("nontemporal", nt)):
+                job.set_option(k, v)
+            job.p.copy_(p0); job.v.copy_(v0); job.avg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            G.run_steps(sc, job, g, fused=fused)
+            what = f"tile={tile} unroll={u} batch={nb} nt={nt} fused={fused}"
+            assert np.array_equal(bits(job.avg.cpu().numpy()), bits(ref.avg)), what
+            assert np.array_equal(bits(job.p.cpu().numpy()), bits(ref.p)), what
+            assert np.array_equal(bits(job.v.cpu().numpy()), bits(ref.v)), what
+    finally:
+        job.close()
+
+
+def _reduce_only(rank_grads: np.ndarray, A: int, fused=False):
+    """One bucket, one step through the library; returns the averaged gradient."""
+    N, L = rank_grads.shape
+    job = ESTJob(N, L, [(0, L)], A)
+    try:
+        src = torch.from_numpy(np.ascontiguousarray(rank_grads)).to(G.DEV)
+        for e in range(N):
+            job.accumulate(e, 0, src[e])
+        if fused:
+            job.reduce_sgd_step(0.0, 0.0)
+        else:
+            job.ring_order_reduce()
+        job.sync()
+        return job.avg.cpu().numpy()
+    finally:
+        job.close()
+
+
+def test_order_witness_on_gpu():
+    m = 1000
+    vals = np.array([2.0 ** 24, 1.0, -(2.0 ** 24), 1.0], dtype=np.float32)
+    g = np.repeat(vals[:, None], 4 * m, axis=1)
+    for fused in (False, True):
+        avg = _reduce_only(g, 1, fused)
+        want = np.repeat(np.array([0.25, 0.5, 0.5, 0.0], dtype=np.float32), m)
+        assert np.array_equal(bits(avg), bits(want))
+    assert np.array_equal(bits(_reduce_only(g, 1)), bits(oracle.ring_order_reduce(g, A=1)))
+
+
+def test_n1_identity_signed_zero_and_denormals():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal(5000).astype(np.float32)
+    x[:6] = [-0.0, 0.0, 1e-45, -1e-40, 1.1754942e-38, -1.1754942e-38]
+    avg = _reduce_only(x[None, :], 4)
+    assert np.array_equal(bits(avg), bits(x))
+
+
+def test_denormal_sums_and_quotients_are_kept():
+    N, L = 4, 4099
+    rng = np.random.default_rng(1)
+    g = (rng.standard_normal((N, L)) * 1e-39).astype(np.float32)      # all denormal
+    g[:, 0] = [1e-45, -1e-45, 0.0, -0.0]
+    want = oracle.ring_order_reduce(g, A=4)
+    assert np.count_nonzero(want) > L // 2 and np.abs(want).max() < 1.2e-38
+    assert np.array_equal(bits(_reduce_only(g, 4)), bits(want))
+    assert np.array_equal(bits(_reduce_only(g, 4, fused=True)), bits(want))
+
+
+@pytest.mark.parametrize("N", [3, 5, 6, 7])
+def test_true_division_for_non_power_of_two(N):
+    xs = np.arange(1, 20001, dtype=np.float32)
+    g = np.zeros((N, xs.size), dtype=np.float32)
+    g[N - 1] = xs
+    want = oracle.ring_order_reduce(g, A=1)
+    got = _reduce_only(g, 1)
+    assert np.array_equal(bits(got), bits(want))
+    assert np.any(got != xs * (np.float32(1) / np.float32(N)))         # a reciprocal multiply would differ
+
+
+def _sgd_only(p, v, g, lr, mu):
+    n = p.size
+    job = ESTJob(1, n, [(0, n)], 1)
+    try:
+        job.p.copy_(torch.from_numpy(p)); job.v.copy_(torch.from_numpy(v)); job.avg.copy_(torch.from_numpy(g))
+        torch.cuda.synchronize()
+        job.sgd_step(lr, mu)
+        job.sync()
+        out = job.p.cpu().numpy(), job.v.cpu().numpy()
+        # same through the fused kernel (N = 1: averaged gradient = gradient)
+        job.p.copy_(torch.from_numpy(p)); job.v.copy_(torch.from_numpy(v))
+        src = torch.from_numpy(g).to(G.DEV)
+        torch.cuda.synchronize()
+        job.accumulate(0, 0, src)
+        job.reduce_sgd_step(lr, mu, store_avg=False)
+        job.sync()
+        fused = job.p.cpu().numpy(), job.v.cpu().numpy()
+        return out, fused
+    finally:
+        job.close()
+
+
+def test_sgd_is_not_contracted_to_fma():
+    e = np.float32(1.0 + 2.0 ** -12)
+    r = np.float32(1.0 + 2.0 ** -11)
+    n = 1030                                            # vector body + scalar tail
+    for p0, v0, g0, lr, mu in ((0.0, e, -r, 0.0, float(e)), (r, 0.0, e, float(e), 0.0)):
+        p = np.full(n, p0, dtype=np.float32); v = np.full(n, v0, dtype=np.float32); g = np.full(n, g0, dtype=np.float32)
+        pw, vw = p.copy(), v.copy()
+        oracle.sgd_momentum(pw, vw, g, lr, mu)
+        for got_p, got_v in _sgd_only(p, v, g, lr, mu):
+            assert np.array_equal(bits(got_p), bits(pw)) and np.array_equal(bits(got_v), bits(vw))
+    assert pw[0] == 0.0
+
+
+def test_sgd_random_parity():
+    rng = np.random.default_rng(3)
+    n = 3 * 4096 + 3
+    p, v, g = (rng.standard_normal(n).astype(np.float32) for _ in range(3))
+    pw, vw = p.copy(), v.copy()
+    oracle.sgd_momentum(pw, vw, g, 0.1, 0.9)
+    for got_p, got_v in _sgd_only(p, v, g, 0.1, 0.9):
+        assert np.array_equal(bits(got_p), bits(pw)) and np.array_equal(bits(got_v), bits(vw))
+
+
+@pytest.mark.parametrize("n,p_drop,off", [(1, 0.1, 0), (15, 0.5, 3), (16, 0.1, 2 ** 32 - 1), (4099, 0.1, 2 ** 40),
+                                           (100003, 0.9, 12345), (64, 0.0, 0), (64, 1.0, 0)])
+def test_dropout_mask_parity(n, p_drop, off):
+    seed = 0xFEEDFACE12345678
+    for misalign in (0, 1):
+        job = ESTJob(2, 4, [(0, 4)], 1, [16])
+        try:
+            st = np.array([seed, off], dtype=np.uint64)
+            job.live_of(0)[0].copy_(torch.from_numpy(st.view(np.uint8)))
+            torch.cuda.synchronize()
+            buf = torch.full((n + 17,), 7, dtype=torch.uint8, device=G.DEV)
+            mask = buf[misalign:misalign + n]
+            job.dropout_mask(0, 0, mask, p_drop)
+            job.sync()
+            want_state = st.copy()
+            want = oracle.dropout_mask(want_state, n, p_drop)
+            assert np.array_equal(mask.cpu().numpy(), want)
+            assert np.all(buf[misalign + n:].cpu().numpy() == 7) and np.all(buf[:misalign].cpu().numpy() == 7)
+            got_state = job.live_of(0)[0].cpu().numpy().view(np.uint64)
+            assert np.array_equal(got_state, want_state)
+        finally:
+            job.close()
+
+
+def test_grouping_invariance_with_switch_and_unaligned_live_tensors():
+    N = 8
+    sc = ragged_scenario(N, 4, 55, steps=3, mask_n=517, bn_channels=(64, 3, 128, 1, 2048))
+    ref = S.run_ddp_reference(sc)
+    gs = [configs.contiguous([8]), configs.contiguous([4, 4]), configs.contiguous([1] * 8, "1x8"),
+          configs.round_robin([3, 5]), configs.reversed_slots(configs.contiguous([2, 6]))]
+    for g in gs:
+        S.assert_same(G.run_gpu(sc, g), ref, g.name)
+        S.assert_same(G.run_gpu(sc, g, fused=True, use_switch=True), ref, g.name + " switch")
+
+    # live tensors at odd addresses: the byte path of the context copy.  (The Philox
+    # state has to stay 8-byte aligned for the mask kernel, so only BN moves.)
+    def odd_alloc(nb):
+        base = torch.full((nb + 32,), 0xCD, dtype=torch.uint8, device=G.DEV)
+        return base[16:16 + nb] if nb == 16 else base[1:1 + nb]
+    S.assert_same(G.run_gpu(sc, gs[1], live_alloc=odd_alloc), ref, "unaligned live")
+
+
+def test_regrouping_between_steps_keeps_contexts():
+    """An elasticity event (paper §3.2): ESTs move to other workers between global steps."""
+    N = 6
+    sc = ragged_scenario(N, 1, 77, steps=3, mask_n=99, bn_channels=(5, 16))
+    ref = S.run_ddp_reference(sc)
+    g0, g1, g2 = configs.contiguous([6]), configs.contiguous([2, 4]), configs.round_robin([1, 2, 3])
+    job = G.make_job(sc, g0)
+    try:
+        G.init_contexts(sc, job)
+        masks = {}
+        for t, g in enumerate((g0, g1, g2)):
+            if t:
+                job.set_grouping(g.worker_of_est, g.slot_of_est)
+            G.run_steps(sc, job, g, masks=masks, steps=[t])
+        S.assert_same(G.collect(sc, job, masks), ref, "regrouped")
+    finally:
+        job.close()
+
+
+def test_state_errors_and_argument_checks():
+    job = ESTJob(2, 1024, [(0, 512), (512, 512)], 4, [16, 64])
+    h = job.h
+    try:
+        g = torch.zeros(512, device=G.DEV)
+        assert B.es_accumulate(h, 2, 0, g.data_ptr()) == B.ES_EINVAL
+        assert B.es_accumulate(h, 0, 2, g.data_ptr()) == B.ES_EINVAL
+        assert B.es_accumulate(h, 0, 0, 0) == B.ES_EINVAL
+        assert B.es_accumulate(h, 0, 0, g.data_ptr() + 2) == B.ES_EINVAL
+        assert B.es_accumulate(h, 0, 0, g.data_ptr()) == B.ES_OK
+        assert B.es_accumulate(h, 0, 0, g.data_ptr()) == B.ES_ESTATE          # twice
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_ESTATE   # not all present
+        assert B.es_set_grouping(h, [0, 1], [0, 0]) == B.ES_ESTATE            # mid-step
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr() + 4) in (B.ES_EINVAL, B.ES_ESTATE)
+        for e, b in ((0, 1), (1, 0)):
+            assert B.es_accumulate(h, e, b, g.data_ptr()) == B.ES_OK
+        # zero-copy production: write into the slot, then only mark it
+        slot = B.es_grad_slot(h, 1, 1)
+        assert slot and B.es_accumulate(h, 1, 1, slot) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr() + 4) == B.ES_EINVAL
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_ESTATE   # new step started
+        assert B.es_ctx_save(h, 2) == B.ES_EINVAL
+        assert B.es_ctx_switch(h, 0, 0) == B.ES_EINVAL
+        assert B.es_ctx_switch(h, 0, 1) == B.ES_OK
+        assert B.es_dropout_mask(h, 0, 1, g.data_ptr(), 4, 0.1) == B.ES_EINVAL   # not a 16-byte segment
+        assert B.es_dropout_mask(h, 0, 0, g.data_ptr(), 4, 1.5) == B.ES_EINVAL
+        assert B.es_set_option(h, "reduce_tile_elems", 100) == B.ES_EINVAL
+        assert B.es_set_option(h, "no_such_option", 1) == B.ES_EINVAL
+        assert B.es_set_grouping(h, [0, 0], [0, 0]) == B.ES_EINVAL
+        assert B.es_set_grouping(h, [0, 2], [0, 0]) == B.ES_EINVAL
+        assert B.es_set_grouping(h, [0, 1], [0, 0]) == B.ES_OK
+        assert B.es_ctx_save(h, 0) == B.ES_ESTATE                             # bindings dropped
+        assert B.es_ctx_switch(h, 0, 1) == B.ES_EINVAL                        # different workers now
+        assert B.es_sync(h) == B.ES_OK
+        st, q = B.es_query(h)
+        assert st == 0 and q["n_params"] == 1024 and q["n_buckets"] == 2 and q["ctx_bytes"] == 80 and q["n_workers"] == 2
+    finally:
+        job.close()
+
+
+def test_zero_copy_slots_match_copied_staging():
+    """A bucket whose gradient already sits in the slot is only marked, not copied."""
+    N, L = 4, 10007
+    rng = np.random.default_rng(9)
+    g = rng.standard_normal((N, L)).astype(np.float32)
+    want = oracle.ring_order_reduce(g, A=4)
+    job = ESTJob(N, L, [(0, L)], 4)
+    try:
+        src = torch.from_numpy(g).to(G.DEV)
+        for e in range(N):
+            job.accumulate(e, 0, src[e])                     # copies into the slots
+        job.ring_order_reduce(); job.sync()
+        assert np.array_equal(bits(job.avg.cpu().numpy()), bits(want))
+        job.avg.zero_(); torch.cuda.synchronize()
+        for e in range(N):                                   # next step: slots still hold the data
+            B.check(B.es_accumulate(job.h, e, 0, B.es_grad_slot(job.h, e, 0)), "es_accumulate")
+        job.ring_order_reduce(); job.sync()
+        assert np.array_equal(bits(job.avg.cpu().numpy()), bits(want))
+    finally:
+        job.close()
