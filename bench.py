@@ -1,0 +1,266 @@
+#!/usr/bin/env python3
+"""Benchmark of the EST step on one MI355X.
+
+One *step* = one global step of the whole hot path on synthetic gradients that
+are already resident in HBM: for every EST its context restore, the staging of
+all its gradient buckets into its context slot, its context save; then the
+ring-ordered N-way reduce and the SGD-momentum update (fused in one kernel by
+default, --split times them as two kernels).
+
+Prints ONE JSON line.  `value` is whole-step throughput on algorithmic bytes;
+`roofline` prices the reduce kernel (the kernel the metric names) against the
+HBM peak from HIP-event timings taken inside the timed region; `kernels` holds
+the same figure for the staging copy; `cpu_baseline` is the CPU oracle timed on
+the host cores for the same step, whose result is also compared bit for bit
+with the GPU's (`zero_ulp`).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
+    ap.add_argument("--split", action="store_true", help="reduce and SGD as two kernels")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value")
+    return ap.parse_args()
+
+
+def est_switch_us(torch, reps=200):
+    """EST switch latency on the BatchNorm context of the ResNet-50 configuration
+    (106 live tensors, 212,480 bytes) plus a 16-byte RNG state."""
+    from paper_2208_14228_amd.job import ESTJob
+    from workloads import shapes
+    segs = [16] + [4 * c for c in shapes.resnet50_bn_channels() for _ in (0, 1)]
+    job = ESTJob(4, 1024, [(0, 1024)], 4, segs)
+    out = {"ctx_bytes": sum(segs), "live_tensors": len(segs)}
+    try:
+        for e in range(4):
+            job.ctx_save(e)
+        job.sync()
+
+        def timed(fn):
+            for i in range(10):
+                fn(i)
+            job.sync()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(job.ctx)
+            t0 = time.perf_counter()
+            for i in range(reps):
+                fn(i)
+            e1.record(job.ctx)
+            job.sync()
+            torch.cuda.synchronize()
+            wall = (time.perf_counter() - t0) / reps * 1e6
+            return e0.elapsed_time(e1) / reps * 1e3, wall
+
+        gpu, wall = timed(lambda i: job.ctx_switch(i % 4, (i + 1) % 4))
+        out["switch_kernel_us"] = round(gpu, 3)
+        out["switch_wall_us"] = round(wall, 3)
+
+        def pair(i):
+            job.ctx_save(i % 4)
+            job.ctx_restore((i + 1) % 4)
+        gpu, wall = timed(pair)
+        out["save_restore_us"] = round(gpu, 3)
+        out["save_restore_wall_us"] = round(wall, 3)
+    finally:
+        job.close()
+    return out
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs the EST step on one GPU only (no collectives, no "
+              "multi-GPU sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2208_14228_amd import binding as B
+    from paper_2208_14228_amd.job import ESTJob
+    from workloads import configs, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; libes has no CPU path", file=sys.stderr)
+        sys.exit(1)
+
+    cfg = configs.config(a.config)
+    lay, N, P = cfg.layout, cfg.n_logical, cfg.layout.n_params
+    g = cfg.groupings[0]
+    dev = "cuda:0"
+    segs = []
+    if cfg.dropout:
+        segs.append(16)
+    segs += [4 * c for c in cfg.bn_channels for _ in (0, 1)]
+
+    job = ESTJob(N, P, lay.buckets, cfg.chunk_align, segs, g.worker_of_est, g.slot_of_est, dev)
+    for kv in a.opt:
+        k, v = kv.split("=")
+        job.set_option(k, int(v))
+    opts = {k: B.es_get_option(job.h, k)[1] for k in
+            ("reduce_tile_elems", "reduce_unroll", "reduce_rank_batch", "nontemporal")}
+
+    # synthetic inputs, resident in HBM before anything is timed
+    src = []
+    for e in range(N):
+        t = torch.empty(P, dtype=torch.float32, device=dev)
+        for b, (off, ln) in enumerate(lay.buckets):
+            synth.gradient(lay, b, cfg.seed, 0, e, dev, out=t[off:off + ln])
+        src.append(t)
+    p0 = synth.params(lay, cfg.seed, dev)
+    mask = torch.empty(32 * 128 * 768, dtype=torch.uint8, device=dev) if cfg.dropout else None
+    for e in range(N):
+        if segs:
+            job.ctx_save(e)
+    job.sync()
+    torch.cuda.synchronize()
+
+    fused = not a.split
+    ev_r = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for _ in range(a.steps)]
+    ev_s = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for _ in range(a.steps)]
+    ev_c = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            for _ in range(a.steps)]
+
+    def step(i=None):
+        if i is not None:
+            job.stage.wait_stream(job.main)      # the interval below must not include the previous reduce
+            ev_c[i][0].record(job.stage)
+        for e in range(N):
+            job.ctx_restore(e)
+            if mask is not None:
+                job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
+            for b, (off, ln) in enumerate(lay.buckets):
+                B.es_accumulate(job.h, e, b, src[e].data_ptr() + 4 * off)
+            job.ctx_save(e)
+        if i is not None:
+            ev_c[i][1].record(job.stage)
+            B.es_stage_fence(job.h)
+            ev_r[i][0].record(job.main)
+        if fused:
+            job.reduce_sgd_step(cfg.lr, cfg.momentum, store_avg=False)
+            if i is not None:
+                ev_r[i][1].record(job.main)
+        else:
+            job.ring_order_reduce()
+            if i is not None:
+                ev_r[i][1].record(job.main)
+                ev_s[i][0].record(job.main)
+            job.sgd_step(cfg.lr, cfg.momentum)
+            if i is not None:
+                ev_s[i][1].record(job.main)
+
+    # ---- bit check of one step against the CPU oracle, which is timed as the CPU baseline ----
+    cpu = None
+    zero_ulp = None
+    if not a.no_cpu:
+        import oracle
+        from oracle.ddp_reference import DDPReference
+        job.p.copy_(p0); job.v.zero_()
+        torch.cuda.synchronize()
+        step()
+        job.sync(); torch.cuda.synchronize()
+        gp, gv = job.p.cpu().numpy(), job.v.cpu().numpy()
+        host = [t.cpu().numpy() for t in src]
+        ref = DDPReference(N, lay.buckets, P, cfg.chunk_align, cfg.lr, cfg.momentum, p0.cpu().numpy())
+        oracle.lib()
+        t0 = time.perf_counter()
+        ref.global_step(lambda r, b: host[r][lay.buckets[b][0]:lay.buckets[b][0] + lay.buckets[b][1]])
+        dt = time.perf_counter() - t0
+        zero_ulp = bool(np.array_equal(gp.view(np.uint32), ref.p.view(np.uint32)) and
+                        np.array_equal(gv.view(np.uint32), ref.v.view(np.uint32)))
+        cpu_bytes = (N + 1) * 4 * P + 5 * 4 * P
+        cpu = {"value": round(cpu_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "seconds": round(dt, 3),
+               "sample": f"one full global step of config {a.config} (ring all-reduce simulation of all "
+                         f"{lay.n_buckets} buckets among {N} ranks, /N, SGD-momentum), bytes counted as "
+                         f"(N+1)*4P + 5*4P; gradient staging not included"}
+        del host
+
+    # ---- timed region ----
+    job.p.copy_(p0); job.v.zero_()
+    torch.cuda.synchronize()
+    for _ in range(a.warmup):
+        step()
+    job.sync(); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(i)
+    job.sync(); torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_step = dt / a.steps * 1e3
+
+    ctx_bytes = sum(segs)
+    bytes_stage = 2 * N * 4 * P
+    bytes_reduce = (N + 4) * 4 * P if fused else (N + 1) * 4 * P
+    bytes_sgd = 0 if fused else 5 * 4 * P
+    bytes_ctx = 2 * N * ctx_bytes + (N * mask.numel() if mask is not None else 0)
+    total = bytes_stage + bytes_reduce + bytes_sgd + bytes_ctx
+
+    red_ms = sum(x.elapsed_time(y) for x, y in ev_r) / a.steps
+    stage_ms = sum(x.elapsed_time(y) for x, y in ev_c) / a.steps
+    sgd_ms = (sum(x.elapsed_time(y) for x, y in ev_s) / a.steps) if not fused else None
+    red_gbps = bytes_reduce / (red_ms * 1e-3) / 1e9
+    n_copies = N * sum(1 for _, ln in lay.buckets if ln)
+
+    out = {
+        "metric": "ring-order N-way grad reduce GB/s (% HBM peak); EST switch µs; 0-ULP",
+        "value": round(total / dt * a.steps / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"config {a.config}: {cfg.name}-shaped gradient set, N={N} ESTs, "
+                               f"P={P} fp32 in {lay.n_buckets} DDP buckets, grouping {g.name}",
+                   "n_logical": N, "n_params": P, "n_buckets": lay.n_buckets,
+                   "mode": "fused reduce+sgd" if fused else "reduce, then sgd", **opts},
+        "step_bytes": {"staging": bytes_stage, "reduce": bytes_reduce, "sgd": bytes_sgd,
+                       "context": bytes_ctx, "total": total},
+        "roofline": {"bound": "hbm", "kernel": "k_ring_reduce" + (" (fused SGD)" if fused else ""),
+                     "achieved": round(red_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(red_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": bytes_reduce, "avg_launch_ms": round(red_ms, 4)},
+        "kernels": {
+            "k_copy_f4 (staging)": {
+                "launches_per_step": n_copies, "bytes_per_step": bytes_stage,
+                "stream_ms_per_step": round(stage_ms, 4),
+                "achieved": round(bytes_stage / (stage_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                "frac": round(bytes_stage / (stage_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        },
+        "reduce_pct_hbm_peak": round(100 * red_gbps / HBM_PEAK_GBPS, 2),
+        "zero_ulp": zero_ulp,
+        "cpu_baseline": cpu,
+    }
+    if sgd_ms is not None:
+        out["kernels"]["k_sgd"] = {"avg_launch_ms": round(sgd_ms, 4),
+                                   "achieved": round(bytes_sgd / (sgd_ms * 1e-3) / 1e9, 1),
+                                   "unit": "GB/s"}
+    job.close()
+    if not a.no_switch:
+        out["est_switch"] = est_switch_us(torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

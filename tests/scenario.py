@@ -113,7 +113,9 @@ def assert_same(a: Result, b: Result, what: str = "") -> None:
     assert a.masks == b.masks, (what, "dropout masks")
 
 
-def run_ddp_reference(sc: Scenario) -> Result:
+def run_ddp_reference(sc: Scenario, gen_device="cpu") -> Result:
+    """``gen_device`` only chooses where torch evaluates the seeded input generator
+    (same bits on either device); the reference itself runs on the host."""
     from oracle.ddp_reference import DDPReference
     N = sc.n_logical
     seeds = [philox_seed(sc, e) for e in range(N)] if sc.mask_n else None
@@ -127,7 +129,7 @@ def run_ddp_reference(sc: Scenario) -> Result:
                                bn_delta(sc, t, r).numpy() if sc.bn_len else None)
             if m is not None:
                 masks[(t, r)] = digest(m)
-        ref.global_step(lambda r, b: grad(sc, t, r, b).numpy())
+        ref.global_step(lambda r, b: grad(sc, t, r, b, gen_device).cpu().numpy())
     return Result(ref.p, ref.v, ref.avg, ref.philox, ref.bn, masks)
 
 

@@ -289,3 +289,13 @@ def test_zero_copy_slots_match_copied_staging():
         assert np.array_equal(bits(job.avg.cpu().numpy()), bits(want))
     finally:
         job.close()
+
+
+def test_input_generator_gives_the_same_bits_on_cpu_and_gpu():
+    from workloads import shapes
+    lay = buckets.ddp_buckets(shapes.resnet50())
+    for b in (0, 3):
+        a = synth.gradient(lay, b, 0x5EED0002, 1, 5)
+        c = synth.gradient(lay, b, 0x5EED0002, 1, 5, G.DEV).cpu()
+        assert torch.equal(a.view(torch.int32), c.view(torch.int32))
+    assert torch.equal(synth.params(lay, 9).view(torch.int32), synth.params(lay, 9, G.DEV).cpu().view(torch.int32))

@@ -68,3 +68,15 @@ def test_generator_windows_and_streams():
     # per-tensor scale: the 1-D tensors (fan_in 1) are much larger than conv weights
     t_off, t_len, fan = lay.tensors[0]
     assert fan == 1 and t_len == 1000          # fc.bias comes first in reversed order
+
+
+def test_values_at_matches_ranges():
+    lay = buckets.ddp_buckets(shapes.resnet50())
+    idx = torch.cat([torch.arange(a, b) for a, b in ((0, 50), (990, 1100), (2049000, 2049100),
+                                                     (lay.n_params - 77, lay.n_params))])
+    got = synth.values_at(lay, idx, 3, 1, 6)
+    want = torch.cat([synth.values(lay, a, b, 3, 1, 6) for a, b in ((0, 50), (990, 1100), (2049000, 2049100),
+                                                                    (lay.n_params - 77, lay.n_params))])
+    assert torch.equal(got, want)
+    p = synth.values_at(lay, idx, 3, 0, synth.STREAM_PARAM, 1.0, True)
+    assert torch.equal(p, synth.params(lay, 3)[idx])

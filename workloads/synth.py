@@ -68,6 +68,33 @@ def field_sums(lo: int, hi: int, key: int, device="cpu") -> torch.Tensor:
     return s - 131070
 
 
+def field_sums_at(idx: torch.Tensor, key: int) -> torch.Tensor:
+    """int64 tensor of s for an arbitrary int64 tensor of flat indices."""
+    x = idx + _s64(key)
+    z = x + _s64(0x9E3779B97F4A7C15)
+    z = (z ^ _lsr(z, 30)) * _s64(0xBF58476D1CE4E5B9)
+    z = (z ^ _lsr(z, 27)) * _s64(0x94D049BB133111EB)
+    z = z ^ _lsr(z, 31)
+    s = (z & 0xFFFF) + (_lsr(z, 16) & 0xFFFF) + (_lsr(z, 32) & 0xFFFF) + (_lsr(z, 48) & 0xFFFF)
+    return s - 131070
+
+
+def scales_at(layout: Layout, idx: torch.Tensor, sigma0: float, use_fan_in: bool) -> torch.Tensor:
+    """fp32 per-element scale for arbitrary flat indices (same values as ``scales``)."""
+    starts = torch.tensor([off for off, _, _ in layout.tensors], dtype=torch.int64, device=idx.device)
+    vals = torch.tensor([(sigma0 / sqrt(f) if use_fan_in else sigma0) / STD_S for _, _, f in layout.tensors],
+                        dtype=torch.float32, device=idx.device)
+    which = torch.searchsorted(starts, idx, right=True) - 1
+    return vals[which]
+
+
+def values_at(layout: Layout, idx: torch.Tensor, seed: int, step: int, stream: int,
+              sigma0: float = 1e-2, use_fan_in: bool = True) -> torch.Tensor:
+    """fp32 synthetic values at arbitrary flat indices; same bits as ``values`` on ranges."""
+    s = field_sums_at(idx, stream_key(seed, step, stream)).to(torch.float32)
+    return s * scales_at(layout, idx, sigma0, use_fan_in)
+
+
 def scales(layout: Layout, lo: int, hi: int, sigma0: float, use_fan_in: bool,
            device="cpu") -> torch.Tensor:
     """fp32 per-element scale for flat indices [lo, hi): sigma0 / sqrt(fan_in) / STD_S."""
