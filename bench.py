@@ -38,50 +38,54 @@ def parse():
     ap.add_argument("--split", action="store_true", help="reduce and SGD as two kernels")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
+    ap.add_argument("--streams", choices=["one", "three"], default="one",
+                    help="one in-order stream (default: nothing to overlap with in this benchmark) or "
+                         "separate main/ctx/stage streams wired with events")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
     return ap.parse_args()
 
 
 def est_switch_us(torch, reps=200):
     """EST switch latency on the BatchNorm context of the ResNet-50 configuration
-    (106 live tensors, 212,480 bytes) plus a 16-byte RNG state."""
+    (106 live tensors, 212,480 bytes) plus a 16-byte RNG state: the fused
+    save+restore kernel, and a save followed by a restore, per stream mode."""
     from paper_2208_14228_amd.job import ESTJob
     from workloads import shapes
     segs = [16] + [4 * c for c in shapes.resnet50_bn_channels() for _ in (0, 1)]
-    job = ESTJob(4, 1024, [(0, 1024)], 4, segs)
     out = {"ctx_bytes": sum(segs), "live_tensors": len(segs)}
-    try:
-        for e in range(4):
-            job.ctx_save(e)
-        job.sync()
-
-        def timed(fn):
-            for i in range(10):
-                fn(i)
+    for mode in ("one", "three"):
+        job = ESTJob(4, 1024, [(0, 1024)], 4, segs, use_streams=mode)
+        try:
+            for e in range(4):
+                job.ctx_save(e)
             job.sync()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(job.ctx)
-            t0 = time.perf_counter()
-            for i in range(reps):
-                fn(i)
-            e1.record(job.ctx)
-            job.sync()
-            torch.cuda.synchronize()
-            wall = (time.perf_counter() - t0) / reps * 1e6
-            return e0.elapsed_time(e1) / reps * 1e3, wall
 
-        gpu, wall = timed(lambda i: job.ctx_switch(i % 4, (i + 1) % 4))
-        out["switch_kernel_us"] = round(gpu, 3)
-        out["switch_wall_us"] = round(wall, 3)
+            def timed(fn):
+                for i in range(10):
+                    fn(i)
+                job.sync()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(job.ctx)
+                t0 = time.perf_counter()
+                for i in range(reps):
+                    fn(i)
+                e1.record(job.ctx)
+                job.sync()
+                torch.cuda.synchronize()
+                wall = (time.perf_counter() - t0) / reps * 1e6
+                return e0.elapsed_time(e1) / reps * 1e3, wall
 
-        def pair(i):
-            job.ctx_save(i % 4)
-            job.ctx_restore((i + 1) % 4)
-        gpu, wall = timed(pair)
-        out["save_restore_us"] = round(gpu, 3)
-        out["save_restore_wall_us"] = round(wall, 3)
-    finally:
-        job.close()
+            def pair(i):
+                job.ctx_save(i % 4)
+                job.ctx_restore((i + 1) % 4)
+
+            gpu, wall = timed(lambda i: job.ctx_switch(i % 4, (i + 1) % 4))
+            gpu2, wall2 = timed(pair)
+            out[f"streams_{mode}"] = {"switch_us": round(gpu, 3), "switch_wall_us": round(wall, 3),
+                                      "save_then_restore_us": round(gpu2, 3),
+                                      "save_then_restore_wall_us": round(wall2, 3)}
+        finally:
+            job.close()
     return out
 
 
@@ -112,7 +116,8 @@ def main():
         segs.append(16)
     segs += [4 * c for c in cfg.bn_channels for _ in (0, 1)]
 
-    job = ESTJob(N, P, lay.buckets, cfg.chunk_align, segs, g.worker_of_est, g.slot_of_est, dev)
+    job = ESTJob(N, P, lay.buckets, cfg.chunk_align, segs, g.worker_of_est, g.slot_of_est, dev,
+                 use_streams=a.streams)
     for kv in a.opt:
         k, v = kv.split("=")
         job.set_option(k, int(v))
@@ -144,7 +149,8 @@ def main():
 
     def step(i=None):
         if i is not None:
-            job.stage.wait_stream(job.main)      # the interval below must not include the previous reduce
+            if job.stage is not job.main:
+                job.stage.wait_stream(job.main)  # the interval below must not include the previous reduce
             ev_c[i][0].record(job.stage)
         for e in range(N):
             job.ctx_restore(e)
@@ -234,7 +240,8 @@ def main():
         "config": {"workload": f"config {a.config}: {cfg.name}-shaped gradient set, N={N} ESTs, "
                                f"P={P} fp32 in {lay.n_buckets} DDP buckets, grouping {g.name}",
                    "n_logical": N, "n_params": P, "n_buckets": lay.n_buckets,
-                   "mode": "fused reduce+sgd" if fused else "reduce, then sgd", **opts},
+                   "mode": "fused reduce+sgd" if fused else "reduce, then sgd",
+                   "streams": a.streams, **opts},
         "step_bytes": {"staging": bytes_stage, "reduce": bytes_reduce, "sgd": bytes_sgd,
                        "context": bytes_ctx, "total": total},
         "roofline": {"bound": "hbm", "kernel": "k_ring_reduce" + (" (fused SGD)" if fused else ""),
@@ -256,6 +263,16 @@ def main():
         out["kernels"]["k_sgd"] = {"avg_launch_ms": round(sgd_ms, 4),
                                    "achieved": round(bytes_sgd / (sgd_ms * 1e-3) / 1e9, 1),
                                    "unit": "GB/s"}
+    # HBM traffic of the reduce kernel is not measurable from inside the process: it is taken
+    # from the committed rocprofv3 counter summary of this same command, when there is one
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
+            tr = json.load(fh).get(f"config{a.config}_{'fused' if fused else 'split'}")
+        if tr and not a.opt:
+            out["roofline"]["traffic"] = tr["traffic_bytes"]
+            out["roofline"]["traffic_source"] = "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)"
+    except (OSError, ValueError):
+        pass
     job.close()
     if not a.no_switch:
         out["est_switch"] = est_switch_us(torch)

