@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
     ap.add_argument("--split", action="store_true", help="reduce and SGD as two kernels")
+    ap.add_argument("--per-bucket", action="store_true",
+                    help="stage with one es_accumulate launch per bucket instead of es_accumulate_batch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
     ap.add_argument("--streams", choices=["one", "three"], default="one",
@@ -140,6 +142,8 @@ def main():
     torch.cuda.synchronize()
 
     fused = not a.split
+    all_buckets = list(range(lay.n_buckets))
+    src_ptrs = [[src[e].data_ptr() + 4 * off for off, _ in lay.buckets] for e in range(N)]
     ev_r = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             for _ in range(a.steps)]
     ev_s = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
@@ -156,8 +160,11 @@ def main():
             job.ctx_restore(e)
             if mask is not None:
                 job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
-            for b, (off, ln) in enumerate(lay.buckets):
-                B.es_accumulate(job.h, e, b, src[e].data_ptr() + 4 * off)
+            if a.per_bucket:
+                for b, (off, ln) in enumerate(lay.buckets):
+                    B.es_accumulate(job.h, e, b, src[e].data_ptr() + 4 * off)
+            else:
+                B.es_accumulate_batch(job.h, e, all_buckets, src_ptrs[e])
             job.ctx_save(e)
         if i is not None:
             ev_c[i][1].record(job.stage)
@@ -227,7 +234,7 @@ def main():
     stage_ms = sum(x.elapsed_time(y) for x, y in ev_c) / a.steps
     sgd_ms = (sum(x.elapsed_time(y) for x, y in ev_s) / a.steps) if not fused else None
     red_gbps = bytes_reduce / (red_ms * 1e-3) / 1e9
-    n_copies = N * sum(1 for _, ln in lay.buckets if ln)
+    n_copies = N * sum(1 for _, ln in lay.buckets if ln) if a.per_bucket else N
 
     out = {
         "metric": "ring-order N-way grad reduce GB/s (% HBM peak); EST switch µs; 0-ULP",
@@ -241,7 +248,8 @@ def main():
                                f"P={P} fp32 in {lay.n_buckets} DDP buckets, grouping {g.name}",
                    "n_logical": N, "n_params": P, "n_buckets": lay.n_buckets,
                    "mode": "fused reduce+sgd" if fused else "reduce, then sgd",
-                   "streams": a.streams, **opts},
+                   "streams": a.streams,
+                   "staging": "per bucket" if a.per_bucket else "batched per EST", **opts},
         "step_bytes": {"staging": bytes_stage, "reduce": bytes_reduce, "sgd": bytes_sgd,
                        "context": bytes_ctx, "total": total},
         "roofline": {"bound": "hbm", "kernel": "k_ring_reduce" + (" (fused SGD)" if fused else ""),
@@ -249,7 +257,7 @@ def main():
                      "frac": round(red_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                      "bytes_per_launch": bytes_reduce, "avg_launch_ms": round(red_ms, 4)},
         "kernels": {
-            "k_copy_f4 (staging)": {
+            ("k_copy_f4" if a.per_bucket else "k_copy_runs") + " (staging)": {
                 "launches_per_step": n_copies, "bytes_per_step": bytes_stage,
                 "stream_ms_per_step": round(stage_ms, 4),
                 "achieved": round(bytes_stage / (stage_ms * 1e-3) / 1e9, 1), "unit": "GB/s",

@@ -164,6 +164,18 @@ int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in);
  */
 int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_grad_bucket);
 
+/*
+ * es_accumulate for several buckets of one EST at once (same rules per bucket).
+ *   buckets         HOST array of n distinct bucket indices
+ *   d_grad_buckets  HOST array of n DEVICE pointers, one source per bucket
+ * All 16-byte-aligned sources are copied by a single kernel launch; sources that
+ * continue each other in memory for buckets that are adjacent in the parameter
+ * space are merged into one contiguous run.  Validation covers the whole batch
+ * before anything is enqueued or marked.
+ */
+int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
+                        const float* const* d_grad_buckets);
+
 /* DEVICE address of est's slot for `bucket` (NULL on bad arguments).  Changes at es_set_grouping. */
 float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket);
 

@@ -52,6 +52,8 @@ _SIGS = {
     "es_ctx_save": (ctypes.c_int, [_VP, ctypes.c_uint32]),
     "es_ctx_switch": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
     "es_accumulate": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP]),
+    "es_accumulate_batch": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32,
+                                           ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(_VP)]),
     "es_grad_slot": (_VP, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
     "es_stage_fence": (ctypes.c_int, [_VP]),
     "es_dropout_mask": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP,
@@ -127,6 +129,15 @@ def es_ctx_restore(h, est): return lib().es_ctx_restore(h, est)
 def es_ctx_save(h, est): return lib().es_ctx_save(h, est)
 def es_ctx_switch(h, est_out, est_in): return lib().es_ctx_switch(h, est_out, est_in)
 def es_accumulate(h, est, bucket, d_grad): return lib().es_accumulate(h, est, bucket, d_grad)
+
+
+def es_accumulate_batch(h, est, buckets: Sequence[int], d_grads: Sequence[int]) -> int:
+    n = len(buckets)
+    b = (ctypes.c_uint32 * max(1, n))(*buckets)
+    g = (_VP * max(1, n))(*d_grads)
+    return lib().es_accumulate_batch(h, est, n, b, g)
+
+
 def es_grad_slot(h, est, bucket): return lib().es_grad_slot(h, est, bucket) or 0
 def es_stage_fence(h): return lib().es_stage_fence(h)
 

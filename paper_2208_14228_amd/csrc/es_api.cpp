@@ -438,6 +438,81 @@ int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_gr
     return ES_OK;
 }
 
+int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
+                        const float* const* d_grad_buckets)
+{
+    if (!h || est >= h->N || (n && (!buckets || !d_grad_buckets))) return ES_EINVAL;
+    const size_t nb = h->buckets.size();
+    // validate everything first: a failing call must enqueue nothing and mark nothing
+    for (uint32_t k = 0; k < n; ++k) {
+        const uint32_t b = buckets[k];
+        if (b >= nb) return ES_EINVAL;
+        const uint64_t len = h->buckets[b].len_elems;
+        const float* src = d_grad_buckets[k];
+        if (len && (!src || (((uintptr_t)src) & 3))) return ES_EINVAL;
+        for (uint32_t j = 0; j < k; ++j)
+            if (buckets[j] == b) return ES_ESTATE;
+        if (h->accumulated[(size_t)est * nb + b]) return ES_ESTATE;
+        const float* dst = es_grad_slot(h, est, b);
+        if (len && src != dst) {
+            const uintptr_t a = (uintptr_t)src, d = (uintptr_t)dst, sz = len * sizeof(float);
+            if (a < d + sz && d < a + sz) return ES_EINVAL;
+        }
+    }
+    bool ordered = false;
+    CopyRuns runs;
+    runs.n_runs = 0;
+    runs.first_block[0] = 0;
+    auto flush = [&]() -> int {
+        if (runs.n_runs == 0) return ES_OK;
+        ES_HIP(h, launch_copy_runs(h->s_stage, runs));
+        runs.n_runs = 0;
+        runs.first_block[0] = 0;
+        return ES_OK;
+    };
+    for (uint32_t k = 0; k < n; ++k) {
+        const uint32_t b = buckets[k];
+        const uint64_t len = h->buckets[b].len_elems;
+        const float* src = d_grad_buckets[k];
+        float* dst = es_grad_slot(h, est, b);
+        if (len && src != dst) {
+            if (!ordered) {
+                int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
+                if (rc != ES_OK) return rc;
+                ordered = true;
+            }
+            if ((((uintptr_t)src | (uintptr_t)dst) & 15) != 0) {
+                ES_HIP(h, launch_copy_f32(h->s_stage, dst, src, len));      // unaligned: own launch
+            } else {
+                // extend the previous run when source and destination both continue it
+                uint32_t& nr = runs.n_runs;
+                if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst &&
+                    (runs.n[nr - 1] & 3) == 0) {
+                    runs.n[nr - 1] += len;
+                } else {
+                    if (nr == (uint32_t)kMaxRuns) {
+                        int rc = flush();
+                        if (rc != ES_OK) return rc;
+                    }
+                    runs.dst[nr] = dst;
+                    runs.src[nr] = src;
+                    runs.n[nr] = len;
+                    ++nr;
+                }
+                const uint64_t vec = runs.n[nr - 1] >> 2;
+                uint64_t blocks = (vec + kBlock - 1) / kBlock;
+                if (blocks == 0) blocks = 1;
+                if (runs.first_block[nr - 1] + blocks > 0x7fffffffull) return ES_EINVAL;
+                runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;
+            }
+            h->stage_pending = true;
+        }
+        h->accumulated[(size_t)est * nb + b] = 1;
+        h->n_accumulated++;
+    }
+    return flush();
+}
+
 int es_stage_fence(es_handle* h)
 {
     if (!h) return ES_EINVAL;

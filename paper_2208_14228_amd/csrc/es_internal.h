@@ -48,6 +48,17 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
 // dst[0..n) <- src[0..n) floats (any 4-byte alignment)
 hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n);
 
+// Several contiguous runs copied by one launch (batched gradient staging).
+constexpr int kMaxRuns = 32;
+struct CopyRuns {
+    float*       dst[kMaxRuns];
+    const float* src[kMaxRuns];
+    uint64_t     n[kMaxRuns];               // floats; dst and src 16-byte aligned
+    uint32_t     first_block[kMaxRuns + 1]; // prefix sums of workgroups per run
+    uint32_t     n_runs;
+};
+hipError_t launch_copy_runs(hipStream_t s, const CopyRuns& runs);
+
 enum CtxDir { kSave = 0, kRestore = 1, kSwitch = 2 };
 // kSave:    slot_a <- live;  kRestore: live <- slot_a;
 // kSwitch:  slot_a <- live, then live <- slot_b (per byte, same lane)

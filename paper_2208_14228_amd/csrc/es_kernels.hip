@@ -324,6 +324,37 @@ hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t
     return hipGetLastError();
 }
 
+// Batched staging: the runs arrive as a kernel argument (no table upload); a
+// workgroup finds its run by scanning the prefix sums (wave-uniform, scalar).
+__global__ __launch_bounds__(kBlock) void k_copy_runs(const CopyRuns runs)
+{
+    uint32_t r = 0;
+    while (r + 1 < runs.n_runs && blockIdx.x >= runs.first_block[r + 1]) ++r;
+    const uint64_t n = runs.n[r];
+    const uint64_t nvec = n >> 2;
+    const float* __restrict__ src = runs.src[r];
+    float* __restrict__ dst = runs.dst[r];
+    const uint32_t b = blockIdx.x - runs.first_block[r];
+    const uint64_t i = (uint64_t)b * kBlock + threadIdx.x;
+    if (i < nvec) {
+        const f4 x = ld4<true>(src + 4 * i);
+        __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
+    }
+    if (b == 0) {
+        const uint64_t e = 4 * nvec + threadIdx.x;
+        if (e < n) dst[e] = src[e];
+    }
+}
+
+hipError_t launch_copy_runs(hipStream_t s, const CopyRuns& runs)
+{
+    if (runs.n_runs == 0) return hipSuccess;
+    const uint32_t blocks = runs.first_block[runs.n_runs];
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_copy_runs, dim3(blocks), dim3(kBlock), 0, s, runs);
+    return hipGetLastError();
+}
+
 __global__ __launch_bounds__(kBlock) void k_copy_bytes(uint8_t* __restrict__ dst,
                                                        const uint8_t* __restrict__ src, uint64_t n16)
 {

@@ -83,6 +83,12 @@ class ESTJob:
         assert grad.dtype == torch.float32 and grad.is_contiguous() and grad.numel() == self.buckets[b][1]
         B.check(B.es_accumulate(self.h, e, b, grad.data_ptr()), "es_accumulate", self.h)
 
+    def accumulate_batch(self, e, buckets, grads):
+        for b, g in zip(buckets, grads):
+            assert g.dtype == torch.float32 and g.is_contiguous() and g.numel() == self.buckets[b][1]
+        B.check(B.es_accumulate_batch(self.h, e, list(buckets), [g.data_ptr() for g in grads]),
+                "es_accumulate_batch", self.h)
+
     def dropout_mask(self, e, seg, mask: torch.Tensor, p: float):
         assert mask.dtype == torch.uint8 and mask.is_contiguous()
         B.check(B.es_dropout_mask(self.h, e, seg, mask.data_ptr(), mask.numel(), p),

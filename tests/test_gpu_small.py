@@ -299,3 +299,61 @@ def test_input_generator_gives_the_same_bits_on_cpu_and_gpu():
         c = synth.gradient(lay, b, 0x5EED0002, 1, 5, G.DEV).cpu()
         assert torch.equal(a.view(torch.int32), c.view(torch.int32))
     assert torch.equal(synth.params(lay, 9).view(torch.int32), synth.params(lay, 9, G.DEV).cpu().view(torch.int32))
+
+
+def test_batched_staging_matches_per_bucket_staging():
+    """es_accumulate_batch: merged contiguous runs, separate tensors, unaligned sources,
+    empty buckets, more runs than one launch holds."""
+    N = 3
+    lens = [4096 + 8, 0, 12, 1000, 7] + [64] * 40          # 45 buckets, some not multiples of 4
+    lay = buckets.custom(lens, fan_in=1)
+    rng = np.random.default_rng(4)
+    g = rng.standard_normal((N, lay.n_params)).astype(np.float32)
+    want = np.concatenate([oracle.ring_order_reduce(np.ascontiguousarray(g[:, o:o + l]), A=1)
+                           for o, l in lay.buckets])
+    for variant in ("flat", "separate", "shifted"):
+        job = ESTJob(N, lay.n_params, lay.buckets, 1)
+        try:
+            keep = []
+            for e in range(N):
+                if variant == "flat":                        # one flat source: runs merge
+                    flat = torch.from_numpy(g[e]).to(G.DEV)
+                    srcs = [flat[o:o + l] for o, l in lay.buckets]
+                elif variant == "separate":                  # one allocation per bucket
+                    srcs = [torch.from_numpy(g[e, o:o + l].copy()).to(G.DEV) for o, l in lay.buckets]
+                else:                                        # sources at 4-byte (not 16-byte) alignment
+                    flat = torch.zeros(lay.n_params + 1, device=G.DEV)
+                    flat[1:].copy_(torch.from_numpy(g[e]))
+                    srcs = [flat[1 + o:1 + o + l] for o, l in lay.buckets]
+                keep.append(srcs)
+                torch.cuda.synchronize()
+                order = list(range(lay.n_buckets))
+                if e == 1:
+                    order = order[::-1]                      # any order of buckets within a batch
+                job.accumulate_batch(e, order, [srcs[b] for b in order])
+            job.ring_order_reduce(); job.sync()
+            assert np.array_equal(bits(job.avg.cpu().numpy()), bits(want)), variant
+        finally:
+            job.close()
+
+
+def test_batched_staging_validates_before_doing_anything():
+    job = ESTJob(2, 64, [(0, 32), (32, 32)], 4)
+    h = job.h
+    try:
+        g = torch.zeros(64, device=G.DEV)
+        p0, p1 = g.data_ptr(), g.data_ptr() + 128
+        assert B.es_accumulate_batch(h, 0, [0, 0], [p0, p0]) == B.ES_ESTATE       # duplicate in batch
+        assert B.es_accumulate_batch(h, 0, [0, 2], [p0, p1]) == B.ES_EINVAL       # bad bucket
+        assert B.es_accumulate_batch(h, 0, [0, 1], [p0, 0]) == B.ES_EINVAL        # null source
+        assert B.es_accumulate_batch(h, 2, [0], [p0]) == B.ES_EINVAL
+        # nothing was marked by the failed calls
+        assert B.es_accumulate_batch(h, 0, [0, 1], [p0, p1]) == B.ES_OK
+        assert B.es_accumulate_batch(h, 0, [1], [p1]) == B.ES_ESTATE              # already present
+        assert B.es_accumulate_batch(h, 1, [], []) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_ESTATE
+        assert B.es_accumulate_batch(h, 1, [1, 0], [p1, p0]) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_OK
+        assert B.es_sync(h) == B.ES_OK
+    finally:
+        job.close()
