@@ -47,6 +47,7 @@ struct es_handle {
 
     Tile* d_tiles = nullptr;
     uint32_t n_tiles = 0;
+    uint32_t n_big = 0;                         // leading big tiles (see k_ring_reduce_big)
     const float** d_slots = nullptr;            // N device pointers, by virtual rank
 
     std::vector<uint8_t> accumulated;           // [est * n_buckets + bucket]
@@ -58,7 +59,7 @@ struct es_handle {
 
     // one pass per workgroup: 256 lanes x 2 vectors x 4 floats (measured best on MI355X)
     uint32_t tile_elems = 2048;
-    ReduceShape shape{2, 8, 1};
+    ReduceShape shape{2, 8, 1, 0, 1};
 
     int last_hip = 0;
 };
@@ -121,8 +122,9 @@ int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
 // length L covers [min(L, c*CL), min(L, (c+1)*CL)), CL = roundup(ceil(L/N), A).
 int build_tiles(es_handle* h)
 {
-    std::vector<Tile> tiles;
+    std::vector<Tile> big, tiles;
     const uint64_t T = h->tile_elems;
+    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kBlock * h->shape.big_unroll * 4 : 0;
     for (const es_bucket& b : h->buckets) {
         const uint64_t L = b.len_elems;
         if (L == 0) continue;
@@ -130,7 +132,18 @@ int build_tiles(es_handle* h)
         for (uint32_t c = 0; c < h->N; ++c) {
             const uint64_t lo = std::min<uint64_t>(L, (uint64_t)c * CL);
             const uint64_t hi = std::min<uint64_t>(L, lo + CL);
-            for (uint64_t a = lo; a < hi; a += T) {
+            uint64_t a = lo;
+            // full, 16-byte aligned big tiles first; the remainder of the chunk in small tiles
+            if (TB && ((b.offset_elems + lo) & 3) == 0) {
+                for (; a + TB <= hi; a += TB) {
+                    Tile t;
+                    t.off = b.offset_elems + a;
+                    t.len = (uint32_t)TB;
+                    t.rank0 = c;
+                    big.push_back(t);
+                }
+            }
+            for (; a < hi; a += T) {
                 Tile t;
                 t.off = b.offset_elems + a;
                 t.len = (uint32_t)std::min<uint64_t>(T, hi - a);
@@ -139,7 +152,10 @@ int build_tiles(es_handle* h)
             }
         }
     }
-    if (tiles.size() > 0x7fffffffull) return ES_EINVAL;
+    if (big.size() + tiles.size() > 0x7fffffffull) return ES_EINVAL;
+    h->n_big = (uint32_t)big.size();
+    big.insert(big.end(), tiles.begin(), tiles.end());
+    tiles.swap(big);
     if (h->d_tiles) { (void)hipFree(h->d_tiles); h->d_tiles = nullptr; }
     h->n_tiles = (uint32_t)tiles.size();
     if (h->n_tiles) {
@@ -248,6 +264,8 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
         h->slot_of.resize(h->N);
         for (uint32_t e = 0; e < h->N; ++e) h->slot_of[e] = e;
         h->accumulated.assign((size_t)h->N * h->buckets.size(), 0);
+        // many concurrent gradient streams: long contiguous reads per stream pay off (measured)
+        if (h->N >= 16) { h->shape.big_unroll = 32; h->shape.big_rank_batch = 1; }
         h->workers.resize(1);
         h->workers[0].live.assign(h->seg_bytes.size(), nullptr);
     } catch (const std::bad_alloc&) {
@@ -540,7 +558,7 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
     int rc = es_stage_fence(h);
     if (rc != ES_OK) return rc;
-    ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));
+    ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));
     std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
     h->n_accumulated = 0;
     return ES_OK;
@@ -591,6 +609,20 @@ int es_set_option(es_handle* h, const char* name, int64_t value)
         if (rc != ES_OK) { h->tile_elems = old; (void)build_tiles(h); }
         return rc;
     }
+    if (k == "reduce_big_unroll" || k == "reduce_big_rank_batch") {
+        const bool u = k == "reduce_big_unroll";
+        if (u && value != 0 && value != 8 && value != 16 && value != 32) return ES_EINVAL;
+        if (!u && value != 1 && value != 2 && value != 4) return ES_EINVAL;
+        int rc = sync_all(h);
+        if (rc != ES_OK) return rc;
+        int& field = u ? h->shape.big_unroll : h->shape.big_rank_batch;
+        const int old = field;
+        field = (int)value;
+        if (h->shape.big_unroll * h->shape.big_rank_batch > 32) { field = old; return ES_EINVAL; }
+        rc = build_tiles(h);
+        if (rc != ES_OK) { field = old; (void)build_tiles(h); }
+        return rc;
+    }
     if (k == "reduce_unroll") {
         if (value != 1 && value != 2 && value != 4) return ES_EINVAL;
         h->shape.unroll = (int)value;
@@ -617,6 +649,8 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "reduce_unroll") *value = h->shape.unroll;
     else if (k == "reduce_rank_batch") *value = h->shape.rank_batch;
     else if (k == "nontemporal") *value = h->shape.nontemporal;
+    else if (k == "reduce_big_unroll") *value = h->shape.big_unroll;
+    else if (k == "reduce_big_rank_batch") *value = h->shape.big_rank_batch;
     else return ES_EINVAL;
     return ES_OK;
 }

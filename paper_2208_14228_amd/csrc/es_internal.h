@@ -32,12 +32,17 @@ struct ReduceShape {
     int unroll;        // 16-byte vectors per lane per rank
     int rank_batch;    // ranks loaded before adds are issued
     int nontemporal;   // streaming hint on gradient loads
+    int big_unroll;    // 0, or vectors per lane of a big tile (8, 16, 32): see k_ring_reduce_big
+    int big_rank_batch;
 };
 
 // ring-ordered N-way reduce (+ optional fused SGD-momentum).
 //  slots: device table of N slot base pointers indexed by virtual rank.
 //  avg may be null only when p and v are given.
-hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+//  With shape.big_unroll != 0 the first n_big tiles must be full big tiles
+//  (kBlock * big_unroll * 4 elements, offset a multiple of 4) and all others
+//  at most 2048 elements.
+hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles, uint32_t n_big,
                               const float* const* slots, uint32_t N,
                               float* avg, float* p, float* v, float lr, float mu,
                               ReduceShape shape);

@@ -101,18 +101,11 @@ __device__ __forceinline__ void fold_scalar(const float* const ES_CONST_AS* slot
 }
 
 template <int U, int NB, bool NT, bool SGD>
-__global__ __launch_bounds__(kBlock) void k_ring_reduce(const Tile* tiles_g,
-                                                        const float* const* slots_g, uint32_t N,
-                                                        float* __restrict__ avg,
-                                                        float* __restrict__ p,
-                                                        float* __restrict__ v, float lr, float mu)
+__device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots, uint32_t N,
+                                           uint64_t off, uint32_t len, uint32_t rank0,
+                                           float* __restrict__ avg, float* __restrict__ p,
+                                           float* __restrict__ v, float lr, float mu)
 {
-    const Tile ES_CONST_AS* tiles = (const Tile ES_CONST_AS*)tiles_g;
-    const float* const ES_CONST_AS* slots = (const float* const ES_CONST_AS*)slots_g;
-
-    const uint64_t off = tiles[blockIdx.x].off;
-    const uint32_t len = tiles[blockIdx.x].len;
-    const uint32_t rank0 = tiles[blockIdx.x].rank0;
     const float fN = (float)N;
 
     // 16-byte vectors need element offsets that are multiples of 4 (all slot,
@@ -182,6 +175,127 @@ __global__ __launch_bounds__(kBlock) void k_ring_reduce(const Tile* tiles_g,
         fold_scalar<SGD>(slots, N, rank0, fN, vbase + 4ull * nvec + threadIdx.x, avg, p, v, lr, mu);
 }
 
+template <int U, int NB, bool NT, bool SGD>
+__global__ __launch_bounds__(kBlock) void k_ring_reduce(const Tile* tiles_g,
+                                                        const float* const* slots_g, uint32_t N,
+                                                        float* __restrict__ avg,
+                                                        float* __restrict__ p,
+                                                        float* __restrict__ v, float lr, float mu)
+{
+    const Tile ES_CONST_AS* tiles = (const Tile ES_CONST_AS*)tiles_g;
+    const float* const ES_CONST_AS* slots = (const float* const ES_CONST_AS*)slots_g;
+    small_tile<U, NB, NT, SGD>(slots, N, tiles[blockIdx.x].off, tiles[blockIdx.x].len,
+                               tiles[blockIdx.x].rank0, avg, p, v, lr, mu);
+}
+
+// ---------------------------------------------------------------------------
+// Big-tile form of the same kernel for large N.  Measured on MI355X: with many
+// concurrent gradient streams HBM delivers more when each workgroup reads a long
+// contiguous span per stream (128 KiB at UB = 32: 6.2 TB/s at N = 64 against
+// 5.4 TB/s for 8 KiB spans).  A big tile is always full and 16-byte aligned, so
+// addresses are base + constants and nothing is predicated; each wave owns UB
+// consecutive KiB of every stream.  The first n_big workgroups take big tiles,
+// the rest run the small-tile path (chunk remainders, ragged and unaligned
+// pieces) with U = 2, NB = 8.
+// ---------------------------------------------------------------------------
+template <int UB, int NB, bool NT, bool FIRST>
+__device__ __forceinline__ void fold_batch_lin(const float* const ES_CONST_AS* slots, uint32_t N,
+                                               uint32_t r0, uint64_t e0, f4 (&acc)[UB])
+{
+    f4 x[NB][UB];
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        uint32_t r = r0 + j;
+        if (r >= N) r -= N;
+        const float* g = slots[r] + e0;
+#pragma unroll
+        for (int u = 0; u < UB; ++u) x[j][u] = ld4<NT>(g + 256 * u);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+#pragma unroll
+        for (int u = 0; u < UB; ++u) {
+            if (FIRST && j == 0)
+                acc[u] = x[0][u];
+            else
+                acc[u] = acc[u] + x[j][u];
+        }
+    }
+}
+
+template <int U, int NB, bool NT, bool SGD>
+__device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots, uint32_t N,
+                                           uint64_t off, uint32_t len, uint32_t rank0,
+                                           float* __restrict__ avg, float* __restrict__ p,
+                                           float* __restrict__ v, float lr, float mu);
+
+template <int UB, int NBB, bool NT, bool SGD>
+__global__ __launch_bounds__(kBlock) void k_ring_reduce_big(const Tile* tiles_g, uint32_t n_big,
+                                                            const float* const* slots_g, uint32_t N,
+                                                            float* __restrict__ avg,
+                                                            float* __restrict__ p,
+                                                            float* __restrict__ v, float lr, float mu)
+{
+    const Tile ES_CONST_AS* tiles = (const Tile ES_CONST_AS*)tiles_g;
+    const float* const ES_CONST_AS* slots = (const float* const ES_CONST_AS*)slots_g;
+    const uint64_t off = tiles[blockIdx.x].off;
+    const uint32_t len = tiles[blockIdx.x].len;
+    const uint32_t rank0 = tiles[blockIdx.x].rank0;
+    if (blockIdx.x >= n_big) {
+        small_tile<2, 8, NT, SGD>(slots, N, off, len, rank0, avg, p, v, lr, mu);
+        return;
+    }
+    const float fN = (float)N;
+    const uint32_t w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const uint64_t e0 = off + 4ull * ((uint64_t)(w * UB) * 64 + l);
+    f4 acc[UB];
+    uint32_t k;
+    if (N >= (uint32_t)NBB) {
+        fold_batch_lin<UB, NBB, NT, true>(slots, N, rank0, e0, acc);
+        k = NBB;
+    } else {
+        fold_batch_lin<UB, 1, NT, true>(slots, N, rank0, e0, acc);
+        k = 1;
+    }
+    for (; k + NBB <= N; k += NBB) {
+        uint32_t r0 = rank0 + k;
+        if (r0 >= N) r0 -= N;
+        fold_batch_lin<UB, NBB, NT, false>(slots, N, r0, e0, acc);
+    }
+    for (; k < N; ++k) {
+        uint32_t r0 = rank0 + k;
+        if (r0 >= N) r0 -= N;
+        fold_batch_lin<UB, 1, NT, false>(slots, N, r0, e0, acc);
+    }
+    // epilogue four vectors at a time so p and v never need UB registers each
+#pragma unroll
+    for (int u0 = 0; u0 < UB; u0 += 4) {
+        f4 pp[4], vv[4];
+        if constexpr (SGD) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                pp[q] = ld4<false>(p + e0 + 256 * (u0 + q));
+                vv[q] = ld4<false>(v + e0 + 256 * (u0 + q));
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint64_t e = e0 + 256 * (u0 + q);
+            const f4 a = acc[u0 + q] / fN;
+            if (avg) st4(avg + e, a);
+            if constexpr (SGD) {
+                const f4 mv = mu * vv[q];
+                const f4 vn = mv + a;
+                const f4 st = lr * vn;
+                st4(v + e, vn);
+                st4(p + e, pp[q] - st);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 template <int U, int NB>
 static hipError_t launch_reduce_unb(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
                                     const float* const* slots, uint32_t N, float* avg, float* p,
@@ -215,11 +329,50 @@ static hipError_t launch_reduce_u(hipStream_t s, const Tile* tiles, uint32_t n_t
     }
 }
 
-hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
+template <int UB, int NBB>
+static hipError_t launch_reduce_big(hipStream_t s, const Tile* tiles, uint32_t n_tiles, uint32_t n_big,
+                                    const float* const* slots, uint32_t N, float* avg, float* p,
+                                    float* v, float lr, float mu, bool nt)
+{
+    const bool sgd = p != nullptr;
+    dim3 grid(n_tiles), block(kBlock);
+    if (nt) {
+        if (sgd) hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, true, true>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu);
+        else     hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, true, false>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu);
+    } else {
+        if (sgd) hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, false, true>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu);
+        else     hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, false, false>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu);
+    }
+    return hipGetLastError();
+}
+
+template <int UB>
+static hipError_t launch_reduce_big_u(hipStream_t s, const Tile* tiles, uint32_t n_tiles, uint32_t n_big,
+                                      const float* const* slots, uint32_t N, float* avg, float* p,
+                                      float* v, float lr, float mu, ReduceShape sh)
+{
+    const bool nt = sh.nontemporal != 0;
+    switch (sh.big_rank_batch) {
+    case 1: return launch_reduce_big<UB, 1>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
+    case 2: return launch_reduce_big<UB, 2>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
+    case 4: return launch_reduce_big<UB, 4>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles, uint32_t n_big,
                               const float* const* slots, uint32_t N, float* avg, float* p,
                               float* v, float lr, float mu, ReduceShape sh)
 {
     if (n_tiles == 0) return hipSuccess;
+    if (sh.big_unroll) {
+        switch (sh.big_unroll) {
+        case 8:  return launch_reduce_big_u<8>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, sh);
+        case 16: return launch_reduce_big_u<16>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, sh);
+        case 32: return launch_reduce_big_u<32>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, sh);
+        default: return hipErrorInvalidValue;
+        }
+    }
     switch (sh.unroll) {
     case 1: return launch_reduce_u<1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, sh);
     case 2: return launch_reduce_u<2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, sh);

@@ -59,8 +59,36 @@ def test_every_launch_shape_gives_the_same_bits():
             assert np.array_equal(bits(job.avg.cpu().numpy()), bits(ref.avg)), what
             assert np.array_equal(bits(job.p.cpu().numpy()), bits(ref.p)), what
             assert np.array_equal(bits(job.v.cpu().numpy()), bits(ref.v)), what
+        # big tiles (long contiguous reads per stream) mixed with small remainder tiles
+        for ub, nbb, nt, fused in itertools.product((8, 16, 32), (1, 2, 4), (0, 1), (False, True)):
+            if ub * nbb > 32:
+                continue
+            job.set_option("reduce_tile_elems", 2048)
+            job.set_option("reduce_big_unroll", 0)
+            job.set_option("reduce_big_rank_batch", nbb)
+            job.set_option("reduce_big_unroll", ub)
+            job.set_option("nontemporal", nt)
+            job.p.copy_(p0); job.v.copy_(v0); job.avg.fill_(float("nan"))
+            torch.cuda.synchronize()
+            G.run_steps(sc, job, g, fused=fused)
+            what = f"big unroll={ub} batch={nbb} nt={nt} fused={fused}"
+            assert np.array_equal(bits(job.avg.cpu().numpy()), bits(ref.avg)), what
+            assert np.array_equal(bits(job.p.cpu().numpy()), bits(ref.p)), what
+            assert np.array_equal(bits(job.v.cpu().numpy()), bits(ref.v)), what
     finally:
         job.close()
+
+
+def test_big_tiles_cover_large_chunks():
+    """Chunks long enough to hold several big tiles plus a ragged remainder, N = 2 and 5."""
+    for N, A in ((2, 4), (5, 1)):
+        lay = buckets.custom([N * (2 * 32768 + 8192 + 13) + 3, 7, N * 8192], fan_in=3)
+        sc = S.Scenario(N, lay, A, 31 + N, steps=2)
+        ref = S.run_ddp_reference(sc)
+        for ub in (8, 32):
+            got = G.run_gpu(sc, configs.contiguous([N]), fused=(ub == 8),
+                            options={"reduce_big_unroll": ub})
+            S.assert_same(got, ref, f"N={N} big={ub}")
 
 
 def _reduce_only(rank_grads: np.ndarray, A: int, fused=False):
