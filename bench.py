@@ -40,7 +40,7 @@ def parse():
                     help="stage with one es_accumulate launch per bucket instead of es_accumulate_batch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
-    ap.add_argument("--streams", choices=["one", "three"], default="one",
+    ap.add_argument("--streams", choices=["one", "two", "three"], default="one",
                     help="one in-order stream (default: nothing to overlap with in this benchmark) or "
                          "separate main/ctx/stage streams wired with events")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
@@ -55,7 +55,7 @@ def est_switch_us(torch, reps=200):
     from workloads import shapes
     segs = [16] + [4 * c for c in shapes.resnet50_bn_channels() for _ in (0, 1)]
     out = {"ctx_bytes": sum(segs), "live_tensors": len(segs)}
-    for mode in ("one", "three"):
+    for mode in ("one", "two", "three"):
         job = ESTJob(4, 1024, [(0, 1024)], 4, segs, use_streams=mode)
         try:
             for e in range(4):

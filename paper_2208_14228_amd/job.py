@@ -35,10 +35,13 @@ class ESTJob:
             B.check(B.es_set_grouping(self.h, self.worker_of, self.slot_of), "es_set_grouping", self.h)
         self.main = self.ctx = self.stage = None
         # use_streams: True / "three" = separate main, ctx and stage streams (staging and context
-        # traffic overlap with the EST's compute); "one" = a single stream for everything (strictly
-        # in order, no events); False = the null stream
+        # traffic overlap with the EST's compute); "two" = main (also small-state context) + stage;
+        # "one" = a single stream for everything (strictly in order, no events); False = null stream
         if use_streams == "one":
             self.main = self.ctx = self.stage = torch.cuda.Stream(self.device)
+        elif use_streams == "two":
+            self.main = self.ctx = torch.cuda.Stream(self.device)
+            self.stage = torch.cuda.Stream(self.device)
         elif use_streams:
             self.main = torch.cuda.Stream(self.device)
             self.ctx = torch.cuda.Stream(self.device)
