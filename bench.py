@@ -124,7 +124,8 @@ def main():
         k, v = kv.split("=")
         job.set_option(k, int(v))
     opts = {k: B.es_get_option(job.h, k)[1] for k in
-            ("reduce_tile_elems", "reduce_unroll", "reduce_rank_batch", "nontemporal")}
+            ("reduce_tile_elems", "reduce_unroll", "reduce_rank_batch", "nontemporal", "nontemporal_pv",
+             "reduce_big_unroll", "reduce_big_rank_batch")}
 
     # synthetic inputs, resident in HBM before anything is timed
     src = []
@@ -151,13 +152,34 @@ def main():
     ev_c = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             for _ in range(a.steps)]
 
+    # EST e takes over the worker's live state: the first EST of a worker is restored, later
+    # ones switch in with the fused save+restore kernel, the last one is saved at the end
+    sched = g.schedule()
+    prev_of = {e: (sched[k - 1] if k and g.worker_of_est[sched[k - 1]] == g.worker_of_est[e] else None)
+               for k, e in enumerate(sched)}
+    last_of_worker = [e for k, e in enumerate(sched)
+                      if k + 1 == len(sched) or g.worker_of_est[sched[k + 1]] != g.worker_of_est[e]]
+
+    def enter(e):
+        if not segs:
+            return
+        if prev_of[e] is None:
+            job.ctx_restore(e)
+        else:
+            job.ctx_switch(prev_of[e], e)
+
+    def leave():
+        if segs:
+            for e in last_of_worker:
+                job.ctx_save(e)
+
     def step(i=None):
         if i is not None:
             if job.stage is not job.main:
                 job.stage.wait_stream(job.main)  # the interval below must not include the previous reduce
             ev_c[i][0].record(job.stage)
-        for e in range(N):
-            job.ctx_restore(e)
+        for e in sched:
+            enter(e)
             if mask is not None:
                 job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
             if a.per_bucket:
@@ -165,7 +187,7 @@ def main():
                     B.es_accumulate(job.h, e, b, src[e].data_ptr() + 4 * off)
             else:
                 B.es_accumulate_batch(job.h, e, all_buckets, src_ptrs[e])
-            job.ctx_save(e)
+        leave()
         if i is not None:
             ev_c[i][1].record(job.stage)
             B.es_stage_fence(job.h)
@@ -223,6 +245,32 @@ def main():
     dt = time.perf_counter() - t0
     ms_step = dt / a.steps * 1e3
 
+    # the same step when the EST's backward writes its buckets straight into the slots
+    # (es_grad_slot): staging degenerates to marking the buckets present
+    slot_ptrs = [[B.es_grad_slot(job.h, e, b) for b in all_buckets] for e in range(N)]
+
+    def step_zero_copy():
+        for e in sched:
+            enter(e)
+            if mask is not None:
+                job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
+            B.es_accumulate_batch(job.h, e, all_buckets, slot_ptrs[e])
+        leave()
+        if fused:
+            job.reduce_sgd_step(cfg.lr, cfg.momentum, store_avg=False)
+        else:
+            job.ring_order_reduce()
+            job.sgd_step(cfg.lr, cfg.momentum)
+
+    for _ in range(a.warmup):
+        step_zero_copy()
+    job.sync(); torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        step_zero_copy()
+    job.sync(); torch.cuda.synchronize()
+    dt_zc = time.perf_counter() - t0
+
     ctx_bytes = sum(segs)
     bytes_stage = 2 * N * 4 * P
     bytes_reduce = (N + 4) * 4 * P if fused else (N + 1) * 4 * P
@@ -263,6 +311,9 @@ def main():
                 "achieved": round(bytes_stage / (stage_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                 "frac": round(bytes_stage / (stage_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         },
+        "zero_copy_step": {"note": "gradients produced directly in the slots (es_grad_slot), no staging copy",
+                           "ms_per_step": round(dt_zc / a.steps * 1e3, 4),
+                           "value": round((total - bytes_stage) / dt_zc * a.steps / 1e9, 2), "unit": "GB/s"},
         "reduce_pct_hbm_peak": round(100 * red_gbps / HBM_PEAK_GBPS, 2),
         "zero_ulp": zero_ulp,
         "cpu_baseline": cpu,

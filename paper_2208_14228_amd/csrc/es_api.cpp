@@ -59,7 +59,7 @@ struct es_handle {
 
     // one pass per workgroup: 256 lanes x 2 vectors x 4 floats (measured best on MI355X)
     uint32_t tile_elems = 2048;
-    ReduceShape shape{2, 8, 1, 0, 1};
+    ReduceShape shape{2, 8, 1, 0, 1, 0};
 
     int last_hip = 0;
 };
@@ -266,6 +266,8 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
         h->accumulated.assign((size_t)h->N * h->buckets.size(), 0);
         // many concurrent gradient streams: long contiguous reads per stream pay off (measured)
         if (h->N >= 16) { h->shape.big_unroll = 32; h->shape.big_rank_batch = 1; }
+        // parameters + momentum that fit in the Infinity Cache stay cacheable between steps
+        h->shape.nontemporal_pv = (2 * h->P * sizeof(float) > (224ull << 20)) ? 1 : 0;
         h->workers.resize(1);
         h->workers[0].live.assign(h->seg_bytes.size(), nullptr);
     } catch (const std::bad_alloc&) {
@@ -638,6 +640,11 @@ int es_set_option(es_handle* h, const char* name, int64_t value)
         h->shape.nontemporal = (int)value;
         return ES_OK;
     }
+    if (k == "nontemporal_pv") {
+        if (value != 0 && value != 1) return ES_EINVAL;
+        h->shape.nontemporal_pv = (int)value;
+        return ES_OK;
+    }
     return ES_EINVAL;
 }
 
@@ -649,6 +656,7 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "reduce_unroll") *value = h->shape.unroll;
     else if (k == "reduce_rank_batch") *value = h->shape.rank_batch;
     else if (k == "nontemporal") *value = h->shape.nontemporal;
+    else if (k == "nontemporal_pv") *value = h->shape.nontemporal_pv;
     else if (k == "reduce_big_unroll") *value = h->shape.big_unroll;
     else if (k == "reduce_big_rank_batch") *value = h->shape.big_rank_batch;
     else return ES_EINVAL;

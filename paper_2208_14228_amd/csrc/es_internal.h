@@ -34,6 +34,7 @@ struct ReduceShape {
     int nontemporal;   // streaming hint on gradient loads
     int big_unroll;    // 0, or vectors per lane of a big tile (8, 16, 32): see k_ring_reduce_big
     int big_rank_batch;
+    int nontemporal_pv; // streaming hint on parameter / momentum traffic of the fused update
 };
 
 // ring-ordered N-way reduce (+ optional fused SGD-momentum).

@@ -50,7 +50,7 @@ def test_every_launch_shape_gives_the_same_bits():
         for tile, u, nb, nt, fused in itertools.product((256, 1024, 4096, 16384), (1, 2, 4),
                                                         (1, 2, 4, 8, 16), (0, 1), (False, True)):
             for k, v in (("reduce_tile_elems", tile), ("reduce_unroll", u),
-                         ("reduce_rank_batch", nb), ("nontemporal", nt)):
+                         ("reduce_rank_batch", nb), ("nontemporal", nt), ("nontemporal_pv", (u + nb) % 2)):
                 job.set_option(k, v)
             job.p.copy_(p0); job.v.copy_(v0); job.avg.fill_(float("nan"))
             torch.cuda.synchronize()
@@ -68,6 +68,7 @@ def test_every_launch_shape_gives_the_same_bits():
             job.set_option("reduce_big_rank_batch", nbb)
             job.set_option("reduce_big_unroll", ub)
             job.set_option("nontemporal", nt)
+            job.set_option("nontemporal_pv", 1 - nt)
             job.p.copy_(p0); job.v.copy_(v0); job.avg.fill_(float("nan"))
             torch.cuda.synchronize()
             G.run_steps(sc, job, g, fused=fused)
