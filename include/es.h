@@ -226,6 +226,39 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum,
 int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
                        float* d_avg_grad, float lr, float mu);
 
+/*
+ * On-demand checkpoint (paper §3.2 "Adapting to elasticity"; §3.3 D1: the bucket
+ * mapping travels with the checkpoint and is reinstated, never rebuilt).  Taken
+ * between global steps when resources change; the job continues from it with the
+ * ESTs distributed over workers in any other way and produces the same bits.
+ *
+ * The blob holds one copy of the shared state and the contexts of all ESTs:
+ *   header   8 x uint64, little endian: magic 0x3130544B50435345 ("ESCPKT01"),
+ *            n_logical, n_params, n_buckets, chunk_align, n_state_segs,
+ *            ctx_bytes (payload of one context slot), global_step
+ *   buckets  n_buckets x {uint64 offset_elems, uint64 len_elems}
+ *   segments n_state_segs x uint64 size in bytes
+ *   contexts n_logical x ctx_bytes, by virtual rank; inside a context every state
+ *            segment starts at the next multiple of 16 bytes
+ *   param    n_params x fp32, then momentum n_params x fp32
+ *
+ * es_checkpoint_bytes   size of the blob for this handle (0 for a NULL handle).
+ * es_checkpoint_export  host_blob HOST, capacity >= es_checkpoint_bytes; d_param and
+ *                       d_momentum DEVICE (n_params floats each).  Every EST's live state
+ *                       must have been saved (es_ctx_save) and no bucket may be staged
+ *                       (ES_ESTATE).  Synchronises the handle's streams; blocking copies.
+ * es_checkpoint_import  into a handle created with the same n_logical and layout
+ *                       (ES_EINVAL if the blob's header, bucket mapping or state segments
+ *                       differ, or size is wrong); the handle's current grouping decides
+ *                       where each context lands.  Writes d_param, d_momentum, *global_step
+ *                       (may be NULL).  Blocking.
+ */
+uint64_t es_checkpoint_bytes(es_handle* h);
+int es_checkpoint_export(es_handle* h, void* host_blob, uint64_t capacity,
+                         const float* d_param, const float* d_momentum, uint64_t global_step);
+int es_checkpoint_import(es_handle* h, const void* host_blob, uint64_t size,
+                         float* d_param, float* d_momentum, uint64_t* global_step);
+
 /* Blocks until all streams of the handle are idle; returns ES_EHIP if any work failed. */
 int es_sync(es_handle* h);
 

@@ -91,6 +91,26 @@ class ESTModel:
             self.avg[off:off + ln] = ring_order_reduce(ranks, self.A, clobber=True)
         sgd_momentum(self.p, self.v, self.avg, self.lr, self.mu)
 
+    # On-demand checkpoint (paper section 3.2, "Adapting to elasticity"): the contexts of all
+    # ESTs, keyed by virtual rank, plus ONE copy of the shared state.  A job resumed from it
+    # may spread the ESTs over workers in any other way.
+    def checkpoint(self) -> dict:
+        return {
+            "rng": [self.est_rng(e).copy() for e in range(self.N)] if self.has_rng else None,
+            "bn": [self.est_bn(e).copy() for e in range(self.N)] if self.has_bn else None,
+            "p": self.p.copy(), "v": self.v.copy(),
+        }
+
+    def load_checkpoint(self, ck: dict) -> None:
+        for e in range(self.N):
+            w, s = self.worker_of_est[e], self.slot_of_est[e]
+            if self.has_rng:
+                self.slot_rng[w][s] = ck["rng"][e]
+            if self.has_bn:
+                self.slot_bn[w][s] = ck["bn"][e]
+        self.p[:] = ck["p"]
+        self.v[:] = ck["v"]
+
     def est_rng(self, e: int) -> np.ndarray:
         return self.slot_rng[self.worker_of_est[e]][self.slot_of_est[e]]
 

@@ -61,6 +61,10 @@ _SIGS = {
     "es_ring_order_reduce": (ctypes.c_int, [_VP, _VP]),
     "es_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
     "es_reduce_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
+    "es_checkpoint_bytes": (ctypes.c_uint64, [_VP]),
+    "es_checkpoint_export": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP, ctypes.c_uint64]),
+    "es_checkpoint_import": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP,
+                                            ctypes.POINTER(ctypes.c_uint64)]),
     "es_sync": (ctypes.c_int, [_VP]),
     "es_set_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.c_int64]),
     "es_get_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]),
@@ -157,6 +161,20 @@ def es_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
 
 def es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
     return lib().es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu)
+
+
+def es_checkpoint_bytes(h): return lib().es_checkpoint_bytes(h)
+
+
+def es_checkpoint_export(h, host_addr: int, capacity: int, d_param, d_momentum, global_step: int) -> int:
+    return lib().es_checkpoint_export(h, host_addr, capacity, d_param, d_momentum, global_step)
+
+
+def es_checkpoint_import(h, host_addr: int, size: int, d_param, d_momentum) -> Tuple[int, int]:
+    """Returns (status, global_step)."""
+    step = ctypes.c_uint64()
+    st = lib().es_checkpoint_import(h, host_addr, size, d_param, d_momentum, ctypes.byref(step))
+    return st, step.value
 
 
 def es_sync(h): return lib().es_sync(h)

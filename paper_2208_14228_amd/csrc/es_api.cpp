@@ -591,6 +591,81 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum, float* d
     return reduce_common(h, d_avg_grad, d_param, d_momentum, lr, mu);
 }
 
+namespace {
+constexpr uint64_t kCkptMagic = 0x3130544B50435345ull;   // "ESCPKT01" as little-endian bytes
+
+uint64_t ckpt_bytes(const es_handle* h)
+{
+    return 8 * sizeof(uint64_t) + h->buckets.size() * sizeof(es_bucket) +
+           h->seg_bytes.size() * sizeof(uint64_t) + (uint64_t)h->N * h->ctx_bytes +
+           2 * h->P * sizeof(float);
+}
+}  // namespace
+
+uint64_t es_checkpoint_bytes(es_handle* h) { return h ? ckpt_bytes(h) : 0; }
+
+int es_checkpoint_export(es_handle* h, void* host_blob, uint64_t capacity, const float* d_param,
+                         const float* d_momentum, uint64_t global_step)
+{
+    if (!h || !host_blob || capacity < ckpt_bytes(h)) return ES_EINVAL;
+    if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
+    if (h->n_accumulated != 0) return ES_ESTATE;
+    int rc = sync_all(h);
+    if (rc != ES_OK) return rc;
+    uint8_t* out = (uint8_t*)host_blob;
+    const uint64_t hdr[8] = {kCkptMagic, h->N, h->P, h->buckets.size(), h->A,
+                             h->seg_bytes.size(), h->ctx_bytes, global_step};
+    std::memcpy(out, hdr, sizeof(hdr));
+    out += sizeof(hdr);
+    if (!h->buckets.empty()) std::memcpy(out, h->buckets.data(), h->buckets.size() * sizeof(es_bucket));
+    out += h->buckets.size() * sizeof(es_bucket);
+    if (!h->seg_bytes.empty()) std::memcpy(out, h->seg_bytes.data(), h->seg_bytes.size() * sizeof(uint64_t));
+    out += h->seg_bytes.size() * sizeof(uint64_t);
+    if (h->ctx_bytes)
+        for (uint32_t e = 0; e < h->N; ++e, out += h->ctx_bytes)
+            ES_HIP(h, hipMemcpy(out, ctx_base(h, e), h->ctx_bytes, hipMemcpyDeviceToHost));
+    if (h->P) {
+        ES_HIP(h, hipMemcpy(out, d_param, h->P * sizeof(float), hipMemcpyDeviceToHost));
+        out += h->P * sizeof(float);
+        ES_HIP(h, hipMemcpy(out, d_momentum, h->P * sizeof(float), hipMemcpyDeviceToHost));
+    }
+    return ES_OK;
+}
+
+int es_checkpoint_import(es_handle* h, const void* host_blob, uint64_t size, float* d_param,
+                         float* d_momentum, uint64_t* global_step)
+{
+    if (!h || !host_blob || size != ckpt_bytes(h)) return ES_EINVAL;
+    if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
+    const uint8_t* in = (const uint8_t*)host_blob;
+    uint64_t hdr[8];
+    std::memcpy(hdr, in, sizeof(hdr));
+    in += sizeof(hdr);
+    if (hdr[0] != kCkptMagic || hdr[1] != h->N || hdr[2] != h->P || hdr[3] != h->buckets.size() ||
+        hdr[4] != h->A || hdr[5] != h->seg_bytes.size() || hdr[6] != h->ctx_bytes)
+        return ES_EINVAL;
+    // the recorded bucket mapping and state shape must be the ones this job was created with
+    if (!h->buckets.empty() && std::memcmp(in, h->buckets.data(), h->buckets.size() * sizeof(es_bucket)) != 0)
+        return ES_EINVAL;
+    in += h->buckets.size() * sizeof(es_bucket);
+    if (!h->seg_bytes.empty() && std::memcmp(in, h->seg_bytes.data(), h->seg_bytes.size() * sizeof(uint64_t)) != 0)
+        return ES_EINVAL;
+    in += h->seg_bytes.size() * sizeof(uint64_t);
+    if (h->n_accumulated != 0) return ES_ESTATE;
+    int rc = sync_all(h);
+    if (rc != ES_OK) return rc;
+    if (h->ctx_bytes)
+        for (uint32_t e = 0; e < h->N; ++e, in += h->ctx_bytes)
+            ES_HIP(h, hipMemcpy(ctx_base(h, e), in, h->ctx_bytes, hipMemcpyHostToDevice));
+    if (h->P) {
+        ES_HIP(h, hipMemcpy(d_param, in, h->P * sizeof(float), hipMemcpyHostToDevice));
+        in += h->P * sizeof(float);
+        ES_HIP(h, hipMemcpy(d_momentum, in, h->P * sizeof(float), hipMemcpyHostToDevice));
+    }
+    if (global_step) *global_step = hdr[7];
+    return ES_OK;
+}
+
 int es_sync(es_handle* h)
 {
     if (!h) return ES_EINVAL;

@@ -109,6 +109,21 @@ class ESTJob:
                                      self.avg.data_ptr() if store_avg else 0, lr, mu),
                 "es_reduce_sgd_step", self.h)
 
+    def checkpoint_export(self, global_step: int):
+        """Host blob (numpy uint8) holding all EST contexts, parameters and momentum."""
+        import numpy as np
+        n = B.es_checkpoint_bytes(self.h)
+        blob = np.empty(n, dtype=np.uint8)
+        B.check(B.es_checkpoint_export(self.h, blob.ctypes.data, n, self.p.data_ptr(), self.v.data_ptr(),
+                                       global_step), "es_checkpoint_export", self.h)
+        return blob
+
+    def checkpoint_import(self, blob) -> int:
+        st, step = B.es_checkpoint_import(self.h, blob.ctypes.data, blob.size, self.p.data_ptr(),
+                                          self.v.data_ptr())
+        B.check(st, "es_checkpoint_import", self.h)
+        return step
+
     def sync(self): B.check(B.es_sync(self.h), "es_sync", self.h)
     def set_option(self, name, value): B.check(B.es_set_option(self.h, name, value), "es_set_option", self.h)
 

@@ -133,7 +133,9 @@ def run_ddp_reference(sc: Scenario, gen_device="cpu") -> Result:
     return Result(ref.p, ref.v, ref.avg, ref.philox, ref.bn, masks)
 
 
-def run_est_model(sc: Scenario, g: Grouping) -> Result:
+def run_est_model(sc: Scenario, g: Grouping, regroup_at: Optional[Dict[int, Grouping]] = None) -> Result:
+    """``regroup_at`` maps a step index to the grouping the job continues with from that
+    step on, through an on-demand checkpoint and a fresh model (an elasticity event)."""
     from oracle.est_model import ESTModel
     N = sc.n_logical
     seeds = [philox_seed(sc, e) for e in range(N)] if sc.mask_n else None
@@ -143,6 +145,15 @@ def run_est_model(sc: Scenario, g: Grouping) -> Result:
                  seeds, bn0)
     masks = {}
     for t in range(sc.steps):
+        if regroup_at and t in regroup_at:
+            ck = m.checkpoint()
+            g = regroup_at[t]
+            junk = np.full(sc.layout.n_params, np.nan, dtype=np.float32)
+            m = ESTModel(N, g.worker_of_est, g.slot_of_est, sc.layout.buckets, sc.layout.n_params,
+                         sc.chunk_align, sc.lr, sc.momentum, junk,
+                         [0] * N if sc.mask_n else None,
+                         np.full((N, sc.bn_len), np.nan, dtype=np.float32) if sc.bn_len else None)
+            m.load_checkpoint(ck)
         for e in g.schedule():
             m.ctx_restore(e)
             mk = m.local_step(e, sc.mask_n, sc.p_drop,

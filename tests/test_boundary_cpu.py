@@ -63,6 +63,9 @@ def test_null_handle_is_rejected_everywhere():
     assert B.es_reduce_sgd_step(0, 0, 0, 0, 0.1, 0.9) == B.ES_EINVAL
     assert B.es_set_option(0, "nontemporal", 1) == B.ES_EINVAL
     assert B.es_stage_fence(0) == B.ES_EINVAL
+    assert B.es_checkpoint_bytes(0) == 0
+    assert B.es_checkpoint_export(0, 0, 0, 0, 0, 0) == B.ES_EINVAL
+    assert B.es_checkpoint_import(0, 0, 0, 0, 0)[0] == B.ES_EINVAL
     assert B.es_dropout_mask(0, 0, 0, 0, 0, 0.1) == B.ES_EINVAL
     assert B.es_set_streams(0, 0, 0, 0) == B.ES_EINVAL
     assert B.es_last_hip_error(0) == 0

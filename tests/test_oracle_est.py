@@ -58,3 +58,15 @@ def test_negative_control_swapped_contexts_are_seen():
         em.ESTModel = orig
     with pytest.raises(AssertionError):
         assert_same(got, ref, "broken")
+
+
+def test_checkpoint_and_redistribution_change_nothing():
+    """Paper section 3.2/5.1.1: scale 1 worker -> 3 workers -> 2 workers through on-demand
+    checkpoints; the result equals the uninterrupted N-rank run."""
+    sc = small_scenario(6, A=4, seed=9)
+    sc = Scenario(sc.n_logical, sc.layout, sc.chunk_align, sc.seed, 4, sc.lr, sc.momentum,
+                  sc.mask_n, sc.p_drop, sc.bn_channels)
+    ref = run_ddp_reference(sc)
+    got = run_est_model(sc, configs.contiguous([6]),
+                        regroup_at={1: configs.round_robin([1, 2, 3]), 3: configs.contiguous([4, 2])})
+    assert_same(got, ref, "checkpointed")
