@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--streams", choices=["one", "two", "three"], default="one",
                     help="one in-order stream (default: nothing to overlap with in this benchmark) or "
                          "separate main/ctx/stage streams wired with events")
+    ap.add_argument("--host-slots", action="store_true",
+                    help="memory-pressure mode: gradient slots in pinned host memory (host-link bound)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
     return ap.parse_args()
 
@@ -120,6 +122,9 @@ def main():
 
     job = ESTJob(N, P, lay.buckets, cfg.chunk_align, segs, g.worker_of_est, g.slot_of_est, dev,
                  use_streams=a.streams)
+    if a.host_slots:
+        job.set_option("host_slots", 1)
+        job.set_grouping(g.worker_of_est, g.slot_of_est)
     for kv in a.opt:
         k, v = kv.split("=")
         job.set_option(k, int(v))
@@ -296,11 +301,11 @@ def main():
                                f"P={P} fp32 in {lay.n_buckets} DDP buckets, grouping {g.name}",
                    "n_logical": N, "n_params": P, "n_buckets": lay.n_buckets,
                    "mode": "fused reduce+sgd" if fused else "reduce, then sgd",
-                   "streams": a.streams,
+                   "streams": a.streams, "slots": "pinned host memory" if a.host_slots else "HBM",
                    "staging": "per bucket" if a.per_bucket else "batched per EST", **opts},
         "step_bytes": {"staging": bytes_stage, "reduce": bytes_reduce, "sgd": bytes_sgd,
                        "context": bytes_ctx, "total": total},
-        "roofline": {"bound": "hbm", "kernel": "k_ring_reduce" + (" (fused SGD)" if fused else ""),
+        "roofline": {"bound": "hbm" if not a.host_slots else "host link (not an HBM figure)", "kernel": "k_ring_reduce" + (" (fused SGD)" if fused else ""),
                      "achieved": round(red_gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(red_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                      "bytes_per_launch": bytes_reduce, "avg_launch_ms": round(red_ms, 4)},
@@ -327,7 +332,7 @@ def main():
     try:
         with open(os.path.join(ROOT, "profiles", "traffic.json")) as fh:
             tr = json.load(fh).get(f"config{a.config}_{'fused' if fused else 'split'}")
-        if tr and not a.opt:
+        if tr and not a.opt and not a.host_slots:
             out["roofline"]["traffic"] = tr["traffic_bytes"]
             out["roofline"]["traffic_source"] = "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE)"
     except (OSError, ValueError):

@@ -263,7 +263,12 @@ int es_checkpoint_import(es_handle* h, const void* host_blob, uint64_t size,
 int es_sync(es_handle* h);
 
 /*
- * Launch-shape options (never change results).  Names:
+ * Options (never change results).  Names:
+ *   "host_slots"          0/1: placement of gradient slots at the NEXT es_set_grouping: 1 =
+ *                         pinned host memory mapped into the device (the paper keeps the
+ *                         per-EST gradients in host memory, section 3.2; here it is the
+ *                         memory-pressure mode for N * n_params beyond HBM): staging and
+ *                         reduce run unchanged and reach the gradients over the host link
  *   "reduce_tile_elems"   elements of one bucket chunk handled by one workgroup
  *                         (multiple of 4, 256 .. 65536)
  *   "reduce_unroll"       16-byte vectors per lane in flight per rank (1, 2, 4)

@@ -22,6 +22,7 @@ constexpr uint64_t kSlotAlignBytes = 256;
 struct Worker {
     uint32_t n_slots = 0;
     float* grad_arena = nullptr;        // n_slots * grad_stride floats
+    bool grad_on_host = false;          // arena is pinned host memory mapped into the device
     uint8_t* ctx_arena = nullptr;       // n_slots * ctx_stride bytes
     std::vector<void*> live;            // bound live tensors (device addresses)
     Piece* d_pieces = nullptr;
@@ -58,6 +59,7 @@ struct es_handle {
     bool stage_pending = false;                 // staging copies enqueued since the last fence
 
     // one pass per workgroup: 256 lanes x 2 vectors x 4 floats (measured best on MI355X)
+    bool host_slots = false;                    // where the next arena allocation places gradient slots
     uint32_t tile_elems = 2048;
     ReduceShape shape{2, 8, 1, 0, 1, 0};
 
@@ -94,7 +96,7 @@ uint8_t* ctx_base(const es_handle* h, uint32_t est)
 
 void free_worker(Worker& w)
 {
-    if (w.grad_arena) (void)hipFree(w.grad_arena);
+    if (w.grad_arena) (void)(w.grad_on_host ? hipHostFree(w.grad_arena) : hipFree(w.grad_arena));
     if (w.ctx_arena) (void)hipFree(w.ctx_arena);
     if (w.d_pieces) (void)hipFree(w.d_pieces);
     w = Worker{};
@@ -106,8 +108,13 @@ int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
     const uint64_t gbytes = (uint64_t)n_slots * h->grad_stride * sizeof(float);
     const uint64_t cbytes = (uint64_t)n_slots * h->ctx_stride;
     if (gbytes) {
-        hipError_t e = hipMalloc((void**)&w.grad_arena, gbytes);
-        if (e != hipSuccess) { h->last_hip = (int)e; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
+        // host placement: pinned, device-mapped memory; the staging copy and the reduce then
+        // reach the gradients over the host link with the same kernels (memory-pressure mode)
+        w.grad_on_host = h->host_slots;
+        hipError_t e = w.grad_on_host
+                           ? hipHostMalloc((void**)&w.grad_arena, gbytes, hipHostMallocMapped | hipHostMallocPortable)
+                           : hipMalloc((void**)&w.grad_arena, gbytes);
+        if (e != hipSuccess) { h->last_hip = (int)e; w.grad_arena = nullptr; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
     }
     if (cbytes) {
         hipError_t e = hipMalloc((void**)&w.ctx_arena, cbytes);
@@ -715,6 +722,11 @@ int es_set_option(es_handle* h, const char* name, int64_t value)
         h->shape.nontemporal = (int)value;
         return ES_OK;
     }
+    if (k == "host_slots") {
+        if (value != 0 && value != 1) return ES_EINVAL;
+        h->host_slots = value != 0;
+        return ES_OK;
+    }
     if (k == "nontemporal_pv") {
         if (value != 0 && value != 1) return ES_EINVAL;
         h->shape.nontemporal_pv = (int)value;
@@ -732,6 +744,7 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "reduce_rank_batch") *value = h->shape.rank_batch;
     else if (k == "nontemporal") *value = h->shape.nontemporal;
     else if (k == "nontemporal_pv") *value = h->shape.nontemporal_pv;
+    else if (k == "host_slots") *value = h->host_slots ? 1 : 0;
     else if (k == "reduce_big_unroll") *value = h->shape.big_unroll;
     else if (k == "reduce_big_rank_batch") *value = h->shape.big_rank_batch;
     else return ES_EINVAL;

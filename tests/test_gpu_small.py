@@ -386,3 +386,21 @@ def test_batched_staging_validates_before_doing_anything():
         assert B.es_sync(h) == B.ES_OK
     finally:
         job.close()
+
+
+def test_host_resident_gradient_slots_give_the_same_bits():
+    """Memory-pressure mode: slots in pinned host memory (the paper's placement of EST gradients)."""
+    N = 5
+    sc = ragged_scenario(N, 4, 91, steps=2, mask_n=64, bn_channels=(8,))
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([2, 3])
+    job = G.make_job(sc, configs.contiguous([N]))
+    try:
+        job.set_option("host_slots", 1)
+        job.set_grouping(g.worker_of_est, g.slot_of_est)        # re-allocates the arenas on the host
+        G.init_contexts(sc, job)
+        masks = {}
+        G.run_steps(sc, job, g, fused=True, masks=masks)
+        S.assert_same(G.collect(sc, job, masks), ref, "host slots")
+    finally:
+        job.close()
