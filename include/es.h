@@ -176,6 +176,21 @@ int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_gr
 int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
                         const float* const* d_grad_buckets);
 
+/*
+ * Take ALL buckets of one EST in place, without a staging copy: the next reduce
+ * reads this EST's gradients straight from d_flat_grad.  This is the paper's
+ * treatment of the last EST a worker runs in a global step: it does not copy its
+ * gradients aside, it goes straight to synchronization (section 5.1.3).
+ *   d_flat_grad  DEVICE, n_params floats in flat parameter order (all buckets back
+ *                to back), 16-byte aligned; produced by work already enqueued on
+ *                main; must stay unmodified until the reduce of this step has run.
+ * Counts as the accumulate of every bucket of `est` (ES_ESTATE if one of them is
+ * already present).  At most 8 ESTs per global step (ES_ESTATE beyond that; stage
+ * the others with es_accumulate).  Nothing is enqueued; the effect ends with the
+ * next reduce.
+ */
+int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad);
+
 /* DEVICE address of est's slot for `bucket` (NULL on bad arguments).  Changes at es_set_grouping. */
 float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket);
 
@@ -284,6 +299,26 @@ int es_sync(es_handle* h);
  */
 int es_set_option(es_handle* h, const char* name, int64_t value);
 int es_get_option(es_handle* h, const char* name, int64_t* value);
+
+/*
+ * Host-only planning helper (touches no device): the work decomposition of the
+ * ring-ordered reduce for a layout.  Each tile is a range of the flat parameter
+ * space that lies inside ONE ring chunk of one bucket; start_rank is the virtual
+ * rank whose gradient opens the fold for every element of the tile (= the chunk
+ * index, see es_ring_order_reduce).  The first *n_big tiles are big tiles of
+ * 256 * big_unroll * 4 elements (full, offset a multiple of 4); all others have
+ * at most tile_elems elements.  Tiles are disjoint and cover [0, n_params).
+ *   out       HOST array of `capacity` entries, or NULL to query the counts only
+ * Returns ES_EINVAL for an invalid layout or option value, or capacity too small.
+ */
+typedef struct es_tile {
+    uint64_t offset_elems;
+    uint32_t len_elems;
+    uint32_t start_rank;
+} es_tile;
+int es_plan_tiles(uint32_t n_logical, const es_bucket_layout* layout, uint32_t tile_elems,
+                  uint32_t big_unroll, es_tile* out, uint64_t capacity, uint64_t* n_tiles,
+                  uint64_t* n_big);
 
 /* Sizes the library derived from the layout (HOST out pointers, each may be NULL). */
 int es_query(es_handle* h, uint64_t* n_params, uint32_t* n_buckets, uint64_t* ctx_bytes,

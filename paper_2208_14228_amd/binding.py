@@ -30,6 +30,11 @@ class EsBucketLayout(ctypes.Structure):
                 ("state_seg_bytes", ctypes.POINTER(ctypes.c_uint64))]
 
 
+class EsTile(ctypes.Structure):
+    _fields_ = [("offset_elems", ctypes.c_uint64), ("len_elems", ctypes.c_uint32),
+                ("start_rank", ctypes.c_uint32)]
+
+
 class EsError(RuntimeError):
     def __init__(self, status: int, where: str, hip: int = 0):
         self.status = status
@@ -54,6 +59,7 @@ _SIGS = {
     "es_accumulate": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP]),
     "es_accumulate_batch": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32,
                                            ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(_VP)]),
+    "es_accumulate_in_place": (ctypes.c_int, [_VP, ctypes.c_uint32, _VP]),
     "es_grad_slot": (_VP, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
     "es_stage_fence": (ctypes.c_int, [_VP]),
     "es_dropout_mask": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP,
@@ -68,6 +74,9 @@ _SIGS = {
     "es_sync": (ctypes.c_int, [_VP]),
     "es_set_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.c_int64]),
     "es_get_option": (ctypes.c_int, [_VP, ctypes.c_char_p, ctypes.POINTER(ctypes.c_int64)]),
+    "es_plan_tiles": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(EsBucketLayout), ctypes.c_uint32,
+                                     ctypes.c_uint32, ctypes.POINTER(EsTile), ctypes.c_uint64,
+                                     ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]),
     "es_query": (ctypes.c_int, [_VP, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
                                 ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
                                 ctypes.POINTER(ctypes.c_uint64)]),
@@ -144,6 +153,7 @@ def es_accumulate_batch(h, est, buckets: Sequence[int], d_grads: Sequence[int]) 
     return lib().es_accumulate_batch(h, est, n, b, g)
 
 
+def es_accumulate_in_place(h, est, d_flat_grad): return lib().es_accumulate_in_place(h, est, d_flat_grad)
 def es_grad_slot(h, est, bucket): return lib().es_grad_slot(h, est, bucket) or 0
 def es_stage_fence(h): return lib().es_stage_fence(h)
 
@@ -185,6 +195,29 @@ def es_get_option(h, name: str) -> Tuple[int, int]:
     v = ctypes.c_int64()
     st = lib().es_get_option(h, name.encode(), ctypes.byref(v))
     return st, v.value
+
+
+def _layout(n_params, buckets, chunk_align, state_seg_bytes=()):
+    arr = (EsBucket * max(1, len(buckets)))(*[EsBucket(o, l) for o, l in buckets])
+    segs = (ctypes.c_uint64 * max(1, len(state_seg_bytes)))(*state_seg_bytes)
+    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs)
+    lay._keep = (arr, segs)
+    return lay
+
+
+def es_plan_tiles(n_logical: int, n_params: int, buckets, chunk_align: int, tile_elems: int,
+                  big_unroll: int):
+    """Returns (status, n_big, [(offset, len, start_rank), ...])."""
+    lay = _layout(n_params, buckets, chunk_align)
+    nt, nb = ctypes.c_uint64(), ctypes.c_uint64()
+    st = lib().es_plan_tiles(n_logical, ctypes.byref(lay), tile_elems, big_unroll, None, 0,
+                             ctypes.byref(nt), ctypes.byref(nb))
+    if st:
+        return st, 0, []
+    out = (EsTile * max(1, nt.value))()
+    st = lib().es_plan_tiles(n_logical, ctypes.byref(lay), tile_elems, big_unroll, out, nt.value,
+                             ctypes.byref(nt), ctypes.byref(nb))
+    return st, nb.value, [(t.offset_elems, t.len_elems, t.start_rank) for t in out[:nt.value]]
 
 
 def es_query(h):

@@ -51,6 +51,7 @@ struct es_handle {
     uint32_t n_big = 0;                         // leading big tiles (see k_ring_reduce_big)
     const float** d_slots = nullptr;            // N device pointers, by virtual rank
 
+    InPlace in_place{};                         // ESTs whose gradients the next reduce reads in place
     std::vector<uint8_t> accumulated;           // [est * n_buckets + bucket]
     uint64_t n_accumulated = 0;
 
@@ -125,18 +126,16 @@ int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
     return ES_OK;
 }
 
-// Ring-chunk tile table for the current tile size.  Chunk c of a bucket of
-// length L covers [min(L, c*CL), min(L, (c+1)*CL)), CL = roundup(ceil(L/N), A).
-int build_tiles(es_handle* h)
+// Ring-chunk tile table.  Chunk c of a bucket of length L covers
+// [min(L, c*CL), min(L, (c+1)*CL)), CL = roundup(ceil(L/N), A).  Pure host logic.
+void plan_tiles(const std::vector<es_bucket>& buckets, uint32_t N, uint32_t A, uint64_t T,
+                uint64_t TB, std::vector<Tile>& big, std::vector<Tile>& small)
 {
-    std::vector<Tile> big, tiles;
-    const uint64_t T = h->tile_elems;
-    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kBlock * h->shape.big_unroll * 4 : 0;
-    for (const es_bucket& b : h->buckets) {
+    for (const es_bucket& b : buckets) {
         const uint64_t L = b.len_elems;
         if (L == 0) continue;
-        const uint64_t CL = round_up((L + h->N - 1) / h->N, h->A);
-        for (uint32_t c = 0; c < h->N; ++c) {
+        const uint64_t CL = round_up((L + N - 1) / N, A);
+        for (uint32_t c = 0; c < N; ++c) {
             const uint64_t lo = std::min<uint64_t>(L, (uint64_t)c * CL);
             const uint64_t hi = std::min<uint64_t>(L, lo + CL);
             uint64_t a = lo;
@@ -155,10 +154,17 @@ int build_tiles(es_handle* h)
                 t.off = b.offset_elems + a;
                 t.len = (uint32_t)std::min<uint64_t>(T, hi - a);
                 t.rank0 = c;
-                tiles.push_back(t);
+                small.push_back(t);
             }
         }
     }
+}
+
+int build_tiles(es_handle* h)
+{
+    std::vector<Tile> big, tiles;
+    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kBlock * h->shape.big_unroll * 4 : 0;
+    plan_tiles(h->buckets, h->N, h->A, h->tile_elems, TB, big, tiles);
     if (big.size() + tiles.size() > 0x7fffffffull) return ES_EINVAL;
     h->n_big = (uint32_t)big.size();
     big.insert(big.end(), tiles.begin(), tiles.end());
@@ -169,6 +175,23 @@ int build_tiles(es_handle* h)
         ES_HIP(h, hipMalloc((void**)&h->d_tiles, tiles.size() * sizeof(Tile)));
         ES_HIP(h, hipMemcpy(h->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
     }
+    return ES_OK;
+}
+
+int validate_layout(uint32_t n_logical, const es_bucket_layout* lay)
+{
+    if (!lay || n_logical == 0 || n_logical > 65535) return ES_EINVAL;
+    if (lay->chunk_align == 0 || (lay->n_buckets && !lay->buckets)) return ES_EINVAL;
+    if (lay->n_state_segs && !lay->state_seg_bytes) return ES_EINVAL;
+    uint64_t pos = 0;
+    for (uint32_t b = 0; b < lay->n_buckets; ++b) {
+        if (lay->buckets[b].offset_elems != pos) return ES_EINVAL;        // ascending, disjoint, no gaps
+        if (lay->buckets[b].len_elems > (1ull << 40)) return ES_EINVAL;
+        pos += lay->buckets[b].len_elems;
+    }
+    if (pos != lay->n_params) return ES_EINVAL;
+    for (uint32_t j = 0; j < lay->n_state_segs; ++j)
+        if (lay->state_seg_bytes[j] == 0 || lay->state_seg_bytes[j] > (1ull << 32)) return ES_EINVAL;
     return ES_OK;
 }
 
@@ -237,18 +260,9 @@ extern "C" {
 
 int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
 {
-    if (!out || !lay || n_logical == 0 || n_logical > 65535) return ES_EINVAL;
-    if (lay->chunk_align == 0 || (lay->n_buckets && !lay->buckets)) return ES_EINVAL;
-    if (lay->n_state_segs && !lay->state_seg_bytes) return ES_EINVAL;
-    uint64_t pos = 0;
-    for (uint32_t b = 0; b < lay->n_buckets; ++b) {
-        if (lay->buckets[b].offset_elems != pos) return ES_EINVAL;        // ascending, disjoint, no gaps
-        if (lay->buckets[b].len_elems > (1ull << 40)) return ES_EINVAL;
-        pos += lay->buckets[b].len_elems;
-    }
-    if (pos != lay->n_params) return ES_EINVAL;
-    for (uint32_t j = 0; j < lay->n_state_segs; ++j)
-        if (lay->state_seg_bytes[j] == 0 || lay->state_seg_bytes[j] > (1ull << 32)) return ES_EINVAL;
+    if (!out) return ES_EINVAL;
+    int vrc = validate_layout(n_logical, lay);
+    if (vrc != ES_OK) return vrc;
 
     es_handle* h = new (std::nothrow) es_handle;
     if (!h) return ES_ENOMEM;
@@ -324,9 +338,39 @@ int es_set_streams(es_handle* h, void* main, void* ctx, void* stage)
     return ES_OK;
 }
 
+int es_plan_tiles(uint32_t n_logical, const es_bucket_layout* layout, uint32_t tile_elems,
+                  uint32_t big_unroll, es_tile* out, uint64_t capacity, uint64_t* n_tiles,
+                  uint64_t* n_big)
+try {
+    int rc = validate_layout(n_logical, layout);
+    if (rc != ES_OK) return rc;
+    if (tile_elems < 256 || tile_elems > 65536 || (tile_elems & 3)) return ES_EINVAL;
+    if (big_unroll != 0 && big_unroll != 8 && big_unroll != 16 && big_unroll != 32) return ES_EINVAL;
+    std::vector<es_bucket> buckets(layout->buckets, layout->buckets + layout->n_buckets);
+    std::vector<Tile> big, small;
+    plan_tiles(buckets, n_logical, layout->chunk_align, tile_elems,
+               big_unroll ? (uint64_t)kBlock * big_unroll * 4 : 0, big, small);
+    if (n_tiles) *n_tiles = big.size() + small.size();
+    if (n_big) *n_big = big.size();
+    if (out) {
+        if (capacity < big.size() + small.size()) return ES_EINVAL;
+        uint64_t k = 0;
+        for (const std::vector<Tile>* v : {&big, &small})
+            for (const Tile& t : *v) {
+                out[k].offset_elems = t.off;
+                out[k].len_elems = t.len;
+                out[k].start_rank = t.rank0;
+                ++k;
+            }
+    }
+    return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
+}
+
 int es_set_grouping(es_handle* h, uint32_t n_workers, const uint32_t* worker_of_est,
                     const uint32_t* slot_of_est)
-{
+try {
     if (!h || !worker_of_est || !slot_of_est) return ES_EINVAL;
     std::vector<uint32_t> counts;
     if (!valid_grouping(h->N, n_workers, worker_of_est, slot_of_est, counts)) return ES_EINVAL;
@@ -360,10 +404,12 @@ int es_set_grouping(es_handle* h, uint32_t n_workers, const uint32_t* worker_of_
     h->worker_of.assign(worker_of_est, worker_of_est + h->N);
     h->slot_of.assign(slot_of_est, slot_of_est + h->N);
     return upload_slot_table(h);
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
 }
 
 int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs)
-{
+try {
     if (!h || worker >= h->workers.size()) return ES_EINVAL;
     const size_t ns = h->seg_bytes.size();
     if (ns && !live_ptrs) return ES_EINVAL;
@@ -400,6 +446,8 @@ int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs)
     w.live.assign(live_ptrs, live_ptrs + ns);
     w.bound = true;
     return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
 }
 
 int es_ctx_restore(es_handle* h, uint32_t est)
@@ -540,6 +588,22 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
     return flush();
 }
 
+int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad)
+{
+    if (!h || est >= h->N) return ES_EINVAL;
+    if (h->P && (!d_flat_grad || !aligned16(d_flat_grad))) return ES_EINVAL;
+    const size_t nb = h->buckets.size();
+    for (size_t b = 0; b < nb; ++b)
+        if (h->accumulated[(size_t)est * nb + b]) return ES_ESTATE;
+    if (h->in_place.n == kMaxInPlace) return ES_ESTATE;
+    h->in_place.rank[h->in_place.n] = est;
+    h->in_place.ptr[h->in_place.n] = d_flat_grad;
+    h->in_place.n++;
+    for (size_t b = 0; b < nb; ++b) h->accumulated[(size_t)est * nb + b] = 1;
+    h->n_accumulated += nb;
+    return ES_OK;
+}
+
 int es_stage_fence(es_handle* h)
 {
     if (!h) return ES_EINVAL;
@@ -567,9 +631,16 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
     int rc = es_stage_fence(h);
     if (rc != ES_OK) return rc;
+    // gradients taken in place: point their ranks at caller memory for this launch only
+    ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
     ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));
+    if (h->in_place.n) {
+        for (uint32_t k = 0; k < h->in_place.n; ++k) h->in_place.ptr[k] = slot_base(h, h->in_place.rank[k]);
+        ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
+    }
     std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
     h->n_accumulated = 0;
+    h->in_place.n = 0;
     return ES_OK;
 }
 
@@ -680,7 +751,7 @@ int es_sync(es_handle* h)
 }
 
 int es_set_option(es_handle* h, const char* name, int64_t value)
-{
+try {
     if (!h || !name) return ES_EINVAL;
     const std::string k(name);
     if (k == "reduce_tile_elems") {
@@ -733,6 +804,8 @@ int es_set_option(es_handle* h, const char* name, int64_t value)
         return ES_OK;
     }
     return ES_EINVAL;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
 }
 
 int es_get_option(es_handle* h, const char* name, int64_t* value)

@@ -28,6 +28,17 @@ static_assert(sizeof(Piece) == 24, "Piece layout");
 constexpr uint32_t kPieceBytes = 4096;
 constexpr uint32_t kBlock = 256;
 
+// Entries of the rank -> gradient-base table that are redirected for one reduce
+// (gradients taken in place from caller memory, no staging copy).
+constexpr uint32_t kMaxInPlace = 8;
+struct InPlace {
+    uint32_t     n;
+    uint32_t     rank[kMaxInPlace];
+    const float* ptr[kMaxInPlace];      // flat parameter order, 16-byte aligned
+};
+// table[patch.rank[k]] <- patch.ptr[k], stream-ordered (the values travel as a kernel argument)
+hipError_t launch_patch_slots(hipStream_t s, const float** table, const InPlace& patch);
+
 struct ReduceShape {
     int unroll;        // 16-byte vectors per lane per rank
     int rank_batch;    // ranks loaded before adds are issued

@@ -410,6 +410,19 @@ hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles
     }
 }
 
+// Redirect a few entries of the rank -> gradient-base table in stream order.
+__global__ void k_patch_slots(const float** table, const InPlace patch)
+{
+    if (blockIdx.x == 0 && threadIdx.x < patch.n) table[patch.rank[threadIdx.x]] = patch.ptr[threadIdx.x];
+}
+
+hipError_t launch_patch_slots(hipStream_t s, const float** table, const InPlace& patch)
+{
+    if (patch.n == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_patch_slots, dim3(1), dim3(64), 0, s, table, patch);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // SGD with momentum on the shared replica (paper §3.2), unfused form.
 // ---------------------------------------------------------------------------

@@ -92,6 +92,10 @@ class ESTJob:
         B.check(B.es_accumulate_batch(self.h, e, list(buckets), [g.data_ptr() for g in grads]),
                 "es_accumulate_batch", self.h)
 
+    def accumulate_in_place(self, e, flat_grad: torch.Tensor):
+        assert flat_grad.dtype == torch.float32 and flat_grad.is_contiguous() and flat_grad.numel() == self.P
+        B.check(B.es_accumulate_in_place(self.h, e, flat_grad.data_ptr()), "es_accumulate_in_place", self.h)
+
     def dropout_mask(self, e, seg, mask: torch.Tensor, p: float):
         assert mask.dtype == torch.uint8 and mask.is_contiguous()
         B.check(B.es_dropout_mask(self.h, e, seg, mask.data_ptr(), mask.numel(), p),

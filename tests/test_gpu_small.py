@@ -404,3 +404,61 @@ def test_host_resident_gradient_slots_give_the_same_bits():
         S.assert_same(G.collect(sc, job, masks), ref, "host slots")
     finally:
         job.close()
+
+
+def test_in_place_gradients_of_each_workers_last_est():
+    """The last EST a worker runs is not staged (paper section 5.1.3): same bits, small and big tiles."""
+    for N, sizes in ((5, [2, 3]), (16, [1] * 7 + [9]), (3, [3])):
+        lay = buckets.custom([N * (32768 + 2048 + 13) + 3, 0, 7, 4 * N + 1, 4096], fan_in=3)
+        sc = S.Scenario(N, lay, 4 if N != 3 else 1, 200 + N, steps=2)
+        ref = S.run_ddp_reference(sc)
+        g = configs.contiguous(sizes)
+        sched = g.schedule()
+        last = {e for k, e in enumerate(sched)
+                if k + 1 == len(sched) or g.worker_of_est[sched[k + 1]] != g.worker_of_est[e]}
+        job = G.make_job(sc, g, options={"reduce_big_unroll": 8} if N == 5 else None)
+        try:
+            G.init_contexts(sc, job)
+            for t in range(sc.steps):
+                keep = []
+                for e in sched:
+                    with job.stream_ctx():
+                        flat = torch.cat([S.grad(sc, t, e, b, G.DEV) for b in range(lay.n_buckets)])
+                    keep.append(flat)
+                    if e in last and len(last) <= 8:
+                        job.accumulate_in_place(e, flat)
+                    else:
+                        job.accumulate_batch(e, list(range(lay.n_buckets)),
+                                             [flat[o:o + l] for o, l in lay.buckets])
+                if t == 0:
+                    job.ring_order_reduce(); job.sgd_step(sc.lr, sc.momentum)
+                else:
+                    job.reduce_sgd_step(sc.lr, sc.momentum)
+                job.sync(); torch.cuda.synchronize()
+            for name, got, want in (("avg", job.avg, ref.avg), ("p", job.p, ref.p), ("v", job.v, ref.v)):
+                assert np.array_equal(bits(got.cpu().numpy()), bits(want)), (N, name)
+        finally:
+            job.close()
+
+
+def test_in_place_state_rules():
+    job = ESTJob(10, 64, [(0, 32), (32, 32)], 4)
+    h = job.h
+    try:
+        g = torch.zeros(65, device=G.DEV)
+        assert B.es_accumulate_in_place(h, 10, g.data_ptr()) == B.ES_EINVAL
+        assert B.es_accumulate_in_place(h, 0, g.data_ptr() + 4) == B.ES_EINVAL        # not 16-byte aligned
+        assert B.es_accumulate_in_place(h, 0, 0) == B.ES_EINVAL
+        assert B.es_accumulate(h, 0, 1, g.data_ptr()) == B.ES_OK
+        assert B.es_accumulate_in_place(h, 0, g.data_ptr()) == B.ES_ESTATE            # a bucket already present
+        for e in range(1, 9):
+            assert B.es_accumulate_in_place(h, e, g.data_ptr()) == B.ES_OK
+        assert B.es_accumulate_in_place(h, 9, g.data_ptr()) == B.ES_ESTATE            # more than 8 per step
+        assert B.es_accumulate(h, 1, 0, g.data_ptr()) == B.ES_ESTATE                  # already counted
+        assert B.es_accumulate_batch(h, 9, [0, 1], [g.data_ptr(), g.data_ptr() + 128]) == B.ES_OK
+        assert B.es_accumulate(h, 0, 0, g.data_ptr()) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_OK
+        assert B.es_accumulate_in_place(h, 0, g.data_ptr()) == B.ES_OK                # new step, table reset
+        assert B.es_sync(h) == B.ES_OK
+    finally:
+        job.close()

@@ -1,0 +1,65 @@
+"""Host logic of the reduce's work decomposition, checked on the CPU against the
+oracle's chunk geometry: tiles partition the parameter space, never cross a ring
+chunk, carry the chunk index as start rank, and big tiles are full and aligned."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2208_14228_amd import binding as B
+from workloads import buckets, configs, shapes
+
+
+def check(N, lay, A, tile, big):
+    st, n_big, tiles = B.es_plan_tiles(N, lay.n_params, lay.buckets, A, tile, big)
+    assert st == 0
+    covered = np.zeros(lay.n_params, dtype=np.int8) if lay.n_params < 5_000_000 else None
+    total = 0
+    bstart = [o for o, _ in lay.buckets]
+    for k, (off, ln, r0) in enumerate(tiles):
+        assert ln > 0 and r0 < N
+        b = int(np.searchsorted(bstart, off, side="right")) - 1
+        while lay.buckets[b][1] == 0 or off >= lay.buckets[b][0] + lay.buckets[b][1]:
+            b += 1                                            # skip empty buckets at the same offset
+        bo, L = lay.buckets[b]
+        lo, hi = oracle.chunk_bounds(L, N, A, r0)             # the oracle's geometry for chunk r0
+        assert bo + lo <= off and off + ln <= bo + hi, (k, off, ln, r0, b)
+        if k < n_big:
+            assert ln == 256 * big * 4 and off % 4 == 0
+        else:
+            assert ln <= tile
+        total += ln
+        if covered is not None:
+            covered[off:off + ln] += 1
+    assert total == lay.n_params
+    if covered is not None:
+        assert np.all(covered == 1)
+    return n_big, len(tiles)
+
+
+@pytest.mark.parametrize("N,A", [(1, 1), (3, 1), (4, 4), (7, 4), (16, 4), (64, 4)])
+def test_ragged_layouts(N, A):
+    lay = buckets.custom([3 * 4096 + 37, 0, 3, 4096, 1001, 4 * N + 1, 20000 + N, N * 40000 + 5])
+    for tile, big in ((256, 0), (2048, 0), (4096, 8), (2048, 32)):
+        check(N, lay, A, tile, big)
+
+
+def test_benchmark_layouts():
+    for cid in (1, 2, 3, 4, 5):
+        cfg = configs.config(cid)
+        big = 32 if cfg.n_logical >= 16 else 0
+        n_big, n = check(cfg.n_logical, cfg.layout, cfg.chunk_align, 2048, big)
+        if big:                                               # most of the work is in big tiles
+            assert n_big * 32768 > 0.9 * cfg.layout.n_params
+    # the example of the design notes: ResNet-50 bucket 0 among 32 ranks, last chunk 236,360 long
+    st, _, tiles = B.es_plan_tiles(32, 7564264, [(0, 7564264)], 4, 2048, 0)
+    last = [t for t in tiles if t[2] == 31]
+    assert sum(t[1] for t in last) == 236360 and last[0][0] == 31 * 236384
+
+
+def test_rejects_bad_arguments():
+    ok = dict(n_logical=2, n_params=8, buckets=[(0, 8)], chunk_align=1)
+    assert B.es_plan_tiles(2, 8, [(0, 8)], 1, 100, 0)[0] == B.ES_EINVAL      # tile size
+    assert B.es_plan_tiles(2, 8, [(0, 8)], 1, 2048, 5)[0] == B.ES_EINVAL     # big unroll
+    assert B.es_plan_tiles(2, 8, [(0, 4)], 1, 2048, 0)[0] == B.ES_EINVAL     # layout does not cover
+    assert B.es_plan_tiles(0, 8, [(0, 8)], 1, 2048, 0)[0] == B.ES_EINVAL
+    assert B.es_plan_tiles(2, 8, [(0, 8)], 1, 2048, 0)[0] == B.ES_OK
