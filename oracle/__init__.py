@@ -5,7 +5,8 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 Python binding) never does, and this package imports nothing of the product.
 
   es_oracle.c       message-passing ring all-reduce among N simulated ranks,
-                    /N, SGD-momentum, Philox4x32-10 dropout mask (plain C, fp32)
+                    /N, SGD-momentum, Philox4x32-10 dropout mask, fixed-tree sum of
+                    squares (plain C, fp32)
   fold_def.py       the closed form of the same reduction (per-chunk rotated
                     left fold) in numpy: cross-check of the simulator and
                     evaluator of sampled outputs at sizes the simulator cannot hold
@@ -20,7 +21,9 @@ summation error bound vs. exact rational sums; division vs. exact rational
 rounding; SGD vs. exact rationals and a non-contraction witness; Philox vs. an
 independent big-integer implementation, vs. the Philox engine that ships in
 PyTorch's headers, and round-function invertibility; dropout keep rate and
-stream splitting.  No function here is "parity unpinned".
+stream splitting; the fixed-tree sum of squares vs. a numpy twin built from
+reshapes, exact integer cases, single-element cases and the pairwise-summation
+error bound.  No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -71,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.eso_dropout_threshold.restype = ctypes.c_uint64
         L.eso_dropout_mask.argtypes = [u64p, u8p, ctypes.c_uint64, ctypes.c_uint64]
         L.eso_dropout_mask.restype = None
+        L.eso_tree_sumsq.argtypes = [f32p, ctypes.c_uint64]
+        L.eso_tree_sumsq.restype = ctypes.c_float
         _lib = L
     return _lib
 
@@ -144,3 +149,9 @@ def dropout_mask(state: np.ndarray, n: int, p: float) -> np.ndarray:
                            mask.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
                            n, dropout_threshold(p))
     return mask
+
+
+def tree_sumsq(x: np.ndarray) -> np.float32:
+    """Sum of squares of a flat fp32 vector along the fixed tree (see es_oracle.c)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    return np.float32(lib().eso_tree_sumsq(_f32(x) if x.size else None, x.size))

@@ -202,3 +202,57 @@ void eso_dropout_mask(uint64_t state[2], uint8_t *mask, uint64_t n, uint64_t thr
     }
     state[1] += blocks;
 }
+
+/* ------------------------------------------------------------------ *
+ * Fixed-tree sum of squares of a flat vector (for a global gradient norm).
+ * The paper's level D2 (section 3.3) asks for reductions whose result does not
+ * depend on the GPU they run on; the paper fixes thread counts of existing
+ * kernels, this build fixes the summation tree as a function of the data
+ * size alone.  The tree (this build's own definition):
+ *   - the vector is cut into blocks of 4096 elements, missing tail elements
+ *     count as +0;
+ *   - in a block, lane t (0..255) adds, starting from +0, the squares of the
+ *     elements 4*(256*q + t) + c for q = 0..3 (outer) and c = 0..3 (inner);
+ *   - the 256 lane sums are combined by v[t] = v[t] + v[t+s] for t < s,
+ *     s = 128, 64, ..., 1; v[0] is the block's partial;
+ *   - the block partials are combined the same way by one more block: lane t
+ *     adds, from +0, partials t, t+256, t+512, ..., then the same tree.
+ * Every square and every add is rounded to fp32 on its own.
+ * ------------------------------------------------------------------ */
+static float eso_tree256(float v[256])
+{
+    for (int s = 128; s >= 1; s >>= 1)
+        for (int t = 0; t < s; ++t)
+            v[t] = v[t] + v[t + s];
+    return v[0];
+}
+
+float eso_tree_sumsq(const float *x, uint64_t n)
+{
+    uint64_t nblk = (n + 4095) / 4096;
+    float *part = (float *)malloc((nblk ? nblk : 1) * sizeof(float));
+    float v[256];
+    for (uint64_t b = 0; b < nblk; ++b) {
+        for (int t = 0; t < 256; ++t) {
+            float s = 0.0f;
+            for (int q = 0; q < 4; ++q)
+                for (int c = 0; c < 4; ++c) {
+                    uint64_t i = b * 4096 + 4 * (uint64_t)(256 * q + t) + c;
+                    float e = i < n ? x[i] : 0.0f;
+                    float sq = e * e;
+                    s = s + sq;
+                }
+            v[t] = s;
+        }
+        part[b] = eso_tree256(v);
+    }
+    for (int t = 0; t < 256; ++t) {
+        float s = 0.0f;
+        for (uint64_t k = t; k < nblk; k += 256)
+            s = s + part[k];
+        v[t] = s;
+    }
+    float total = eso_tree256(v);
+    free(part);
+    return total;
+}

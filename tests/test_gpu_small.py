@@ -462,3 +462,31 @@ def test_in_place_state_rules():
         assert B.es_sync(h) == B.ES_OK
     finally:
         job.close()
+
+
+def test_handle_lifecycle_and_two_jobs_side_by_side():
+    """Create/destroy cycles give the memory back; two handles do not disturb each other."""
+    free0 = torch.cuda.mem_get_info()[0]
+    for _ in range(20):
+        job = ESTJob(8, 1 << 20, [(0, 1 << 19), (1 << 19, 1 << 19)], 4, [16, 4096])
+        job.set_grouping([0, 0, 1, 1, 2, 2, 3, 3], [0, 1, 0, 1, 0, 1, 0, 1])
+        job.close()
+    torch.cuda.synchronize()
+    assert torch.cuda.mem_get_info()[0] >= free0 - (64 << 20)
+
+    rng = np.random.default_rng(12)
+    a = rng.standard_normal((3, 5000)).astype(np.float32)
+    b = rng.standard_normal((5, 7001)).astype(np.float32)
+    ja, jb = ESTJob(3, 5000, [(0, 5000)], 4), ESTJob(5, 7001, [(0, 7001)], 1)
+    try:
+        sa, sb = torch.from_numpy(a).to(G.DEV), torch.from_numpy(b).to(G.DEV)
+        for e in range(5):                               # interleaved calls on the two handles
+            if e < 3:
+                ja.accumulate(e, 0, sa[e])
+            jb.accumulate(e, 0, sb[e])
+        jb.ring_order_reduce(); ja.ring_order_reduce()
+        ja.sync(); jb.sync()
+        assert np.array_equal(bits(ja.avg.cpu().numpy()), bits(oracle.ring_order_reduce(a, A=4)))
+        assert np.array_equal(bits(jb.avg.cpu().numpy()), bits(oracle.ring_order_reduce(b, A=1)))
+    finally:
+        ja.close(); jb.close()

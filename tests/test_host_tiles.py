@@ -50,7 +50,7 @@ def test_benchmark_layouts():
         n_big, n = check(cfg.n_logical, cfg.layout, cfg.chunk_align, 2048, big)
         if big:                                               # most of the work is in big tiles
             assert n_big * 32768 > 0.9 * cfg.layout.n_params
-    # the example of the design notes: ResNet-50 bucket 0 among 32 ranks, last chunk 236,360 long
+    # a worked example: ResNet-50 bucket 0 (7,564,264 elements) among 32 ranks, last chunk 236,360 long
     st, _, tiles = B.es_plan_tiles(32, 7564264, [(0, 7564264)], 4, 2048, 0)
     last = [t for t in tiles if t[2] == 31]
     assert sum(t[1] for t in last) == 236360 and last[0][0] == 31 * 236384
