@@ -318,6 +318,18 @@ def main():
     job.sync(); torch.cuda.synchronize()
     dt_zc = time.perf_counter() - t0
 
+    # fixed-tree global norm of a vector of the job's size (one read of 4P bytes)
+    out2 = torch.zeros(2, device=dev)
+    for _ in range(3):
+        B.es_grad_sq_norm(job.h, job.p.data_ptr(), out2.data_ptr())
+    n0, n1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n0.record(job.main)
+    for _ in range(a.steps):
+        B.es_grad_sq_norm(job.h, job.p.data_ptr(), out2.data_ptr())
+    n1.record(job.main)
+    job.sync(); torch.cuda.synchronize()
+    norm_ms = n0.elapsed_time(n1) / a.steps
+
     ctx_bytes = sum(segs)
     bytes_stage = 2 * N * 4 * P
     bytes_reduce = (N + 4) * 4 * P if fused else (N + 1) * 4 * P
@@ -371,6 +383,10 @@ def main():
             "note": "the same step captured into a HIP graph and replayed",
             "ms_per_step": round(dt_graph / a.steps * 1e3, 4),
             "value": round(total / dt_graph * a.steps / 1e9, 2), "unit": "GB/s"},
+        "grad_sq_norm": {"note": "fixed-tree global norm (k_sq_partials + k_sq_final), 4P bytes read",
+                         "avg_ms": round(norm_ms, 4),
+                         "achieved": round(4 * P / (norm_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                         "frac": round(4 * P / (norm_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "reduce_pct_hbm_peak": round(100 * red_gbps / HBM_PEAK_GBPS, 2),
         "zero_ulp": zero_ulp,
         "cpu_baseline": cpu,

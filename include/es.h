@@ -242,6 +242,22 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
                        float* d_avg_grad, float lr, float mu);
 
 /*
+ * Global norm of a flat vector of the job's size (e.g. the averaged gradient, for
+ * clipping) along a FIXED summation tree, so the bits depend on the data alone and
+ * not on the GPU, the grid or the launch (the property the paper's level D2 asks of
+ * reductions, section 3.3; the tree is this library's own):
+ *   blocks of 4096 elements, missing tail elements count as +0; in a block lane t
+ *   (0..255) adds, from +0, the squares of elements 4*(256*q + t) + c, q = 0..3 outer,
+ *   c = 0..3 inner; lane sums combine as v[t] += v[t+s] for t < s, s = 128, 64, .., 1;
+ *   block partials combine the same way (lane t first adds partials t, t+256, ...).
+ *   Every square and add is rounded to fp32; no atomics.
+ *   d_vec   DEVICE, n_params floats, 16-byte aligned
+ *   d_out2  DEVICE, 2 floats: [0] sum of squares, [1] its correctly rounded square root
+ * Runs on main.
+ */
+int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2);
+
+/*
  * On-demand checkpoint (paper §3.2 "Adapting to elasticity"; §3.3 D1: the bucket
  * mapping travels with the checkpoint and is reinstated, never rebuilt).  Taken
  * between global steps when resources change; the job continues from it with the

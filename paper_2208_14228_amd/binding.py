@@ -67,6 +67,7 @@ _SIGS = {
     "es_ring_order_reduce": (ctypes.c_int, [_VP, _VP]),
     "es_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
     "es_reduce_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
+    "es_grad_sq_norm": (ctypes.c_int, [_VP, _VP, _VP]),
     "es_checkpoint_bytes": (ctypes.c_uint64, [_VP]),
     "es_checkpoint_export": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP, ctypes.c_uint64]),
     "es_checkpoint_import": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP,
@@ -173,6 +174,7 @@ def es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
     return lib().es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu)
 
 
+def es_grad_sq_norm(h, d_vec, d_out2): return lib().es_grad_sq_norm(h, d_vec, d_out2)
 def es_checkpoint_bytes(h): return lib().es_checkpoint_bytes(h)
 
 

@@ -50,6 +50,7 @@ struct es_handle {
     uint32_t n_tiles = 0;
     uint32_t n_big = 0;                         // leading big tiles (see k_ring_reduce_big)
     const float** d_slots = nullptr;            // N device pointers, by virtual rank
+    float* d_partials = nullptr;                // ceil(P / 4096) block partials of es_grad_sq_norm
 
     InPlace in_place{};                         // ESTs whose gradients the next reduce reads in place
     std::vector<uint8_t> accumulated;           // [est * n_buckets + bucket]
@@ -306,6 +307,10 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
     rc = alloc_worker(h, h->workers[0], h->N);
     if (rc == ES_OK) rc = build_tiles(h);
     if (rc == ES_OK) rc = upload_slot_table(h);
+    if (rc == ES_OK && h->P) {
+        e = hipMalloc((void**)&h->d_partials, ((h->P + 4095) / 4096) * sizeof(float));
+        if (e != hipSuccess) rc = hip_fail(h, e);
+    }
     if (rc != ES_OK) { es_destroy(h); return rc; }
     *out = h;
     return ES_OK;
@@ -320,6 +325,7 @@ int es_destroy(es_handle* h)
     for (Worker& w : h->workers) free_worker(w);
     if (h->d_tiles) (void)hipFree(h->d_tiles);
     if (h->d_slots) (void)hipFree((void*)h->d_slots);
+    if (h->d_partials) (void)hipFree(h->d_partials);
     if (h->ev_main) (void)hipEventDestroy(h->ev_main);
     if (h->ev_ctx) (void)hipEventDestroy(h->ev_ctx);
     if (h->ev_stage) (void)hipEventDestroy(h->ev_stage);
@@ -657,6 +663,14 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_
     if (h->P && (!d_param || !d_momentum || !d_avg_grad)) return ES_EINVAL;
     if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
     ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu));
+    return ES_OK;
+}
+
+int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2)
+{
+    if (!h || !d_out2 || (((uintptr_t)d_out2) & 3)) return ES_EINVAL;
+    if (h->P && (!d_vec || !aligned16(d_vec))) return ES_EINVAL;
+    ES_HIP(h, launch_sq_norm(h->s_main, d_vec, h->P, h->d_partials, d_out2));
     return ES_OK;
 }
 

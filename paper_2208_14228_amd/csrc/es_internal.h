@@ -85,6 +85,10 @@ hipError_t launch_ctx(hipStream_t s, const Piece* pieces, uint32_t n_pieces,
 // generic byte copy used when contexts move between arenas
 hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, uint64_t n);
 
+// out[0] = fixed-tree sum of squares of x[0..n), out[1] = its square root;
+// part: scratch of ceil(n / 4096) floats
+hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part, float* out);
+
 hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, uint64_t n,
                                uint64_t threshold);
 

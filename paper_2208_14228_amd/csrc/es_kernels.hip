@@ -479,6 +479,120 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
 }
 
 // ---------------------------------------------------------------------------
+// Fixed-tree sum of squares of a flat vector (global gradient norm).  In the
+// spirit of the paper's level D2 (section 3.3: reductions must not depend on
+// the GPU they run on) the summation tree is a function of the vector length
+// alone: blocks of 4096 elements; lane t adds the squares of elements
+// 4*(256*q + t) + c, q = 0..3 outer, c = 0..3 inner, starting from +0; the 256
+// lane sums combine as v[t] += v[t+s], s = 128 .. 1; block partials combine the
+// same way in one more workgroup (lane t adds partials t, t+256, ... first).
+// No atomics; wave shuffles (and LDS in the last stage) carry the tree.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float tree256(float s, float* lds)
+{
+    const uint32_t t = threadIdx.x;
+    lds[t] = s;
+    __syncthreads();
+    if (t < 128) {
+        s = s + lds[t + 128];
+        lds[t] = s;
+    }
+    __syncthreads();
+    if (t < 64) {
+        s = s + lds[t + 64];
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s = s + __shfl_down(s, d, 64);
+    }
+    return s;                                           // valid in lane 0
+}
+
+// One WAVE per 4096-element block: hardware lane h plays the tree's lanes h, h+64,
+// h+128 and h+192, so the strides 128 and 64 are adds between its own registers,
+// 32 .. 1 are wave shuffles, and no LDS or barrier is needed; all 16 loads of a
+// lane are in flight before the first add.
+__global__ __launch_bounds__(kBlock) void k_sq_partials(const float* __restrict__ x, uint64_t n,
+                                                        uint64_t nblk, float* __restrict__ part)
+{
+    const uint32_t h = threadIdx.x & 63;
+    const uint64_t blk = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (blk >= nblk) return;                            // whole wave leaves together
+    const uint64_t base = blk * 4096;
+    f4 v[4][4];                                         // [tree lane h + 64 j][q]
+    if (base + 4096 <= n) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j][q] = ld4<true>(x + base + 4ull * (256 * q + 64 * j + h));
+    } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint64_t i = base + 4ull * (256 * q + 64 * j + h);
+                f4 e;
+                e.x = (i + 0 < n) ? x[i + 0] : 0.0f;
+                e.y = (i + 1 < n) ? x[i + 1] : 0.0f;
+                e.z = (i + 2 < n) ? x[i + 2] : 0.0f;
+                e.w = (i + 3 < n) ? x[i + 3] : 0.0f;
+                v[j][q] = e;
+            }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    float s[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float a = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f4 e = v[j][q];
+            a = a + e.x * e.x;
+            a = a + e.y * e.y;
+            a = a + e.z * e.z;
+            a = a + e.w * e.w;
+        }
+        s[j] = a;
+    }
+    float r0 = s[0] + s[2];                             // stride 128: lanes h and h+64
+    float r1 = s[1] + s[3];
+    float r = r0 + r1;                                  // stride 64
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) r = r + __shfl_down(r, d, 64);
+    if (h == 0) part[blk] = r;
+}
+
+__global__ __launch_bounds__(kBlock) void k_sq_final(const float* __restrict__ part, uint64_t nblk,
+                                                     float* __restrict__ out)
+{
+    __shared__ float lds[kBlock];
+    float s = 0.0f;
+    // lane t adds partials t, t+256, ... in that order; eight loads are issued ahead of the adds
+    for (uint64_t k0 = threadIdx.x; k0 < nblk; k0 += 8 * kBlock) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint64_t k = k0 + (uint64_t)j * kBlock;
+            v[j] = part[k < nblk ? k : nblk - 1];
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (k0 + (uint64_t)j * kBlock < nblk) s = s + v[j];
+    }
+    s = tree256(s, lds);
+    if (threadIdx.x == 0) {
+        out[0] = s;
+        out[1] = sqrtf(s);
+    }
+}
+
+hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part, float* out)
+{
+    const uint64_t nblk = (n + 4095) / 4096;
+    if (nblk) hipLaunchKernelGGL(k_sq_partials, dim3((uint32_t)((nblk + 3) / 4)), dim3(kBlock), 0, s, x, n, nblk, part);
+    hipLaunchKernelGGL(k_sq_final, dim3(1), dim3(kBlock), 0, s, part, nblk, out);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Gradient staging: copy one bucket into an EST's context slot (paper §3.2).
 // ---------------------------------------------------------------------------
 // One 16-byte vector per lane and streaming hints on both sides measured fastest
