@@ -164,7 +164,7 @@ void plan_tiles(const std::vector<es_bucket>& buckets, uint32_t N, uint32_t A, u
 int build_tiles(es_handle* h)
 {
     std::vector<Tile> big, tiles;
-    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kBlock * h->shape.big_unroll * 4 : 0;
+    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kReduceBlock * h->shape.big_unroll * 4 : 0;
     plan_tiles(h->buckets, h->N, h->A, h->tile_elems, TB, big, tiles);
     if (big.size() + tiles.size() > 0x7fffffffull) return ES_EINVAL;
     h->n_big = (uint32_t)big.size();
@@ -355,7 +355,7 @@ try {
     std::vector<es_bucket> buckets(layout->buckets, layout->buckets + layout->n_buckets);
     std::vector<Tile> big, small;
     plan_tiles(buckets, n_logical, layout->chunk_align, tile_elems,
-               big_unroll ? (uint64_t)kBlock * big_unroll * 4 : 0, big, small);
+               big_unroll ? (uint64_t)kReduceBlock * big_unroll * 4 : 0, big, small);
     if (n_tiles) *n_tiles = big.size() + small.size();
     if (n_big) *n_big = big.size();
     if (out) {
@@ -581,7 +581,7 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
                     ++nr;
                 }
                 const uint64_t vec = runs.n[nr - 1] >> 2;
-                uint64_t blocks = (vec + kBlock - 1) / kBlock;
+                uint64_t blocks = (vec + kCopyBlock - 1) / kCopyBlock;
                 if (blocks == 0) blocks = 1;
                 if (runs.first_block[nr - 1] + blocks > 0x7fffffffull) return ES_EINVAL;
                 runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;

@@ -27,6 +27,14 @@ static_assert(sizeof(Piece) == 24, "Piece layout");
 
 constexpr uint32_t kPieceBytes = 4096;
 constexpr uint32_t kBlock = 256;
+#ifndef ES_COPY_BLOCK
+#define ES_COPY_BLOCK 64
+#endif
+#ifndef ES_REDUCE_BLOCK
+#define ES_REDUCE_BLOCK 256
+#endif
+constexpr uint32_t kReduceBlock = ES_REDUCE_BLOCK;   // lanes per workgroup of the ring-ordered reduce
+constexpr uint32_t kCopyBlock = ES_COPY_BLOCK;   // lanes per workgroup of the batched staging copy
 
 // Entries of the rank -> gradient-base table that are redirected for one reduce
 // (gradients taken in place from caller memory, no staging copy).

@@ -134,13 +134,13 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
     const uint64_t vbase = off + head;
     const uint32_t tail = len - head - 4 * nvec;
 
-    for (uint32_t i0 = threadIdx.x; i0 < nvec; i0 += kBlock * U) {
+    for (uint32_t i0 = threadIdx.x; i0 < nvec; i0 += kReduceBlock * U) {
         uint64_t e[U];
         bool ok[U];
         f4 acc[U], pp[U], vv[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const uint32_t i = i0 + u * kBlock;
+            const uint32_t i = i0 + u * kReduceBlock;
             ok[u] = i < nvec;
             // a lane without work in this pass re-reads the tile's last vector
             // (in bounds, result dropped) so that no load needs a predicate
@@ -193,7 +193,7 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
 }
 
 template <int U, int NB, int NT, bool SGD>
-__global__ __launch_bounds__(kBlock) void k_ring_reduce(const Tile* tiles_g,
+__global__ __launch_bounds__(kReduceBlock) void k_ring_reduce(const Tile* tiles_g,
                                                         const float* const* slots_g, uint32_t N,
                                                         float* __restrict__ avg,
                                                         float* __restrict__ p,
@@ -248,7 +248,7 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
                                            float* __restrict__ v, float lr, float mu);
 
 template <int UB, int NBB, int NT, bool SGD>
-__global__ __launch_bounds__(kBlock) void k_ring_reduce_big(const Tile* tiles_g, uint32_t n_big,
+__global__ __launch_bounds__(kReduceBlock) void k_ring_reduce_big(const Tile* tiles_g, uint32_t n_big,
                                                             const float* const* slots_g, uint32_t N,
                                                             float* __restrict__ avg,
                                                             float* __restrict__ p,
@@ -319,7 +319,7 @@ static hipError_t launch_reduce_unb(hipStream_t s, const Tile* tiles, uint32_t n
                                     float* v, float lr, float mu, int nt)
 {
     const bool sgd = p != nullptr;
-    dim3 grid(n_tiles), block(kBlock);
+    dim3 grid(n_tiles), block(kReduceBlock);
 #define ES_LAUNCH(NTV, SGDV) \
     hipLaunchKernelGGL((k_ring_reduce<U, NB, NTV, SGDV>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu)
     if (!sgd) {
@@ -358,7 +358,7 @@ static hipError_t launch_reduce_big(hipStream_t s, const Tile* tiles, uint32_t n
                                     float* v, float lr, float mu, int nt)
 {
     const bool sgd = p != nullptr;
-    dim3 grid(n_tiles), block(kBlock);
+    dim3 grid(n_tiles), block(kReduceBlock);
 #define ES_LAUNCH(NTV, SGDV) \
     hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, NTV, SGDV>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu)
     if (!sgd) {
@@ -597,11 +597,11 @@ hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part
 // ---------------------------------------------------------------------------
 // One 16-byte vector per lane and streaming hints on both sides measured fastest
 // on MI355X (about 6.5 TB/s read+write; four vectors per lane: 4.6 TB/s).
-__global__ __launch_bounds__(kBlock) void k_copy_f4(float* __restrict__ dst,
+__global__ __launch_bounds__(kCopyBlock) void k_copy_f4(float* __restrict__ dst,
                                                     const float* __restrict__ src, uint64_t n)
 {
     const uint64_t nvec = n >> 2;
-    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint64_t i = (uint64_t)blockIdx.x * kCopyBlock + threadIdx.x;
     if (i < nvec) {
         const f4 x = ld4<true>(src + 4 * i);
         __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
@@ -623,9 +623,9 @@ hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t
 {
     if (n == 0) return hipSuccess;
     if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
-        uint64_t blocks = ((n >> 2) + kBlock - 1) / kBlock;
+        uint64_t blocks = ((n >> 2) + kCopyBlock - 1) / kCopyBlock;
         if (blocks == 0) blocks = 1;
-        hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
+        hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kCopyBlock), 0, s, dst, src, n);
     } else {
         const uint64_t blocks = (n + kBlock - 1) / kBlock;
         hipLaunchKernelGGL(k_copy_f1, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
@@ -635,16 +635,18 @@ hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t
 
 // Batched staging: the runs arrive as a kernel argument (no table upload); a
 // workgroup finds its run by scanning the prefix sums (wave-uniform, scalar).
-__global__ __launch_bounds__(kBlock) void k_copy_runs(const CopyRuns runs)
+template <int BS>
+__global__ __launch_bounds__(BS) void k_copy_runs(const CopyRuns runs)
 {
     uint32_t r = 0;
-    while (r + 1 < runs.n_runs && blockIdx.x >= runs.first_block[r + 1]) ++r;
+    if (runs.n_runs > 1)
+        while (r + 1 < runs.n_runs && blockIdx.x >= runs.first_block[r + 1]) ++r;
     const uint64_t n = runs.n[r];
     const uint64_t nvec = n >> 2;
     const float* __restrict__ src = runs.src[r];
     float* __restrict__ dst = runs.dst[r];
     const uint32_t b = blockIdx.x - runs.first_block[r];
-    const uint64_t i = (uint64_t)b * kBlock + threadIdx.x;
+    const uint64_t i = (uint64_t)b * BS + threadIdx.x;
     if (i < nvec) {
         const f4 x = ld4<true>(src + 4 * i);
         __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
@@ -660,7 +662,7 @@ hipError_t launch_copy_runs(hipStream_t s, const CopyRuns& runs)
     if (runs.n_runs == 0) return hipSuccess;
     const uint32_t blocks = runs.first_block[runs.n_runs];
     if (blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_copy_runs, dim3(blocks), dim3(kBlock), 0, s, runs);
+    hipLaunchKernelGGL(k_copy_runs<kCopyBlock>, dim3(blocks), dim3(kCopyBlock), 0, s, runs);
     return hipGetLastError();
 }
 
