@@ -183,7 +183,8 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
  * gradients aside, it goes straight to synchronization (section 5.1.3).
  *   d_flat_grad  DEVICE, n_params floats in flat parameter order (all buckets back
  *                to back), 16-byte aligned; produced by work already enqueued on
- *                main; must stay unmodified until the reduce of this step has run.
+ *                main; must stay unmodified until the reduce of this step has run and
+ *                must not overlap that reduce's outputs (ES_EINVAL at the reduce).
  * Counts as the accumulate of every bucket of `est` (ES_ESTATE if one of them is
  * already present).  At most 8 ESTs per global step (ES_ESTATE beyond that; stage
  * the others with es_accumulate).  Nothing is enqueued; the effect ends with the

@@ -443,12 +443,15 @@ try {
             pieces.push_back(pc);
         }
     }
+    // the worker counts as unbound until the new table is in place
+    w.bound = false;
+    w.n_pieces = 0;
     if (w.d_pieces) { (void)hipFree(w.d_pieces); w.d_pieces = nullptr; }
-    w.n_pieces = (uint32_t)pieces.size();
-    if (w.n_pieces) {
+    if (!pieces.empty()) {
         ES_HIP(h, hipMalloc((void**)&w.d_pieces, pieces.size() * sizeof(Piece)));
         ES_HIP(h, hipMemcpy(w.d_pieces, pieces.data(), pieces.size() * sizeof(Piece), hipMemcpyHostToDevice));
     }
+    w.n_pieces = (uint32_t)pieces.size();
     w.live.assign(live_ptrs, live_ptrs + ns);
     w.bound = true;
     return ES_OK;
@@ -637,6 +640,14 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
     int rc = es_stage_fence(h);
     if (rc != ES_OK) return rc;
+    // gradients taken in place must not overlap what this launch writes
+    for (uint32_t k = 0; k < h->in_place.n; ++k) {
+        const uintptr_t g = (uintptr_t)h->in_place.ptr[k], sz = h->P * sizeof(float);
+        for (const float* o : {(const float*)avg, (const float*)p, (const float*)v}) {
+            const uintptr_t b = (uintptr_t)o;
+            if (o && g < b + sz && b < g + sz) return ES_EINVAL;
+        }
+    }
     // gradients taken in place: point their ranks at caller memory for this launch only
     ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
     ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));

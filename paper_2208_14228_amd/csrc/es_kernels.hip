@@ -1,4 +1,5 @@
-// gfx950 (CDNA4) kernels of the EST step.  Wave size 64, 256-lane workgroups.
+// gfx950 (CDNA4) kernels of the EST step.  Wave size 64; 256-lane workgroups except
+// the staging copies, which run one wave per workgroup.
 //
 // Bit-exactness rules that hold for every kernel in this file:
 //  - fp32 IEEE arithmetic, denormals kept, no fused multiply-add (the file is

@@ -457,6 +457,7 @@ def test_in_place_state_rules():
         assert B.es_accumulate(h, 1, 0, g.data_ptr()) == B.ES_ESTATE                  # already counted
         assert B.es_accumulate_batch(h, 9, [0, 1], [g.data_ptr(), g.data_ptr() + 128]) == B.ES_OK
         assert B.es_accumulate(h, 0, 0, g.data_ptr()) == B.ES_OK
+        assert B.es_ring_order_reduce(h, g.data_ptr()) == B.ES_EINVAL                 # output overlaps an in-place gradient
         assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_OK
         assert B.es_accumulate_in_place(h, 0, g.data_ptr()) == B.ES_OK                # new step, table reset
         assert B.es_sync(h) == B.ES_OK
