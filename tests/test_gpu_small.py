@@ -491,3 +491,45 @@ def test_handle_lifecycle_and_two_jobs_side_by_side():
         assert np.array_equal(bits(jb.avg.cpu().numpy()), bits(oracle.ring_order_reduce(b, A=1)))
     finally:
         ja.close(); jb.close()
+
+
+@pytest.mark.parametrize("N,lens", [(257, [100, 3000, 0, 257]), (1024, [5000, 17]), (4096, [4096 * 4 + 3])])
+def test_many_logical_workers(N, lens):
+    """More ranks than elements per chunk, most chunks empty, long add chains."""
+    lay = buckets.custom(lens)
+    rng = np.random.default_rng(N)
+    g = (rng.standard_normal((N, lay.n_params)) * np.exp2(rng.integers(-8, 8, (N, lay.n_params)))).astype(np.float32)
+    want = np.concatenate([oracle.ring_order_reduce(np.ascontiguousarray(g[:, o:o + l]), A=1)
+                           for o, l in lay.buckets if l] or [np.zeros(0, np.float32)])
+    job = ESTJob(N, lay.n_params, lay.buckets, 1)
+    try:
+        src = torch.from_numpy(g).to(G.DEV)
+        allb = list(range(lay.n_buckets))
+        for e in range(N):
+            job.accumulate_batch(e, allb, [src[e, o:o + l] for o, l in lay.buckets])
+        job.ring_order_reduce(); job.sync()
+        assert np.array_equal(bits(job.avg.cpu().numpy()), bits(want))
+    finally:
+        job.close()
+
+
+def test_degenerate_layouts():
+    """No parameters at all, and only empty buckets: every call is a valid no-op."""
+    for bk in ([], [(0, 0)], [(0, 0), (0, 0)]):
+        st, h = B.es_init(3, 0, bk, 4, [])
+        assert st == B.ES_OK and h
+        try:
+            for e in range(3):
+                for b in range(len(bk)):
+                    assert B.es_accumulate(h, e, b, 0) == B.ES_OK
+            assert B.es_ring_order_reduce(h, 0) == B.ES_OK
+            assert B.es_reduce_sgd_step(h, 0, 0, 0, 0.1, 0.9) in (B.ES_OK, B.ES_ESTATE)
+            assert B.es_sgd_step(h, 0, 0, 0, 0.1, 0.9) == B.ES_OK
+            assert B.es_ctx_save(h, 1) == B.ES_OK and B.es_ctx_switch(h, 0, 1) == B.ES_OK
+            assert B.es_sync(h) == B.ES_OK
+            n = B.es_checkpoint_bytes(h)
+            blob = np.zeros(n, dtype=np.uint8)
+            assert B.es_checkpoint_export(h, blob.ctypes.data, n, 0, 0, 3) == B.ES_OK
+            assert B.es_checkpoint_import(h, blob.ctypes.data, n, 0, 0) == (B.ES_OK, 3)
+        finally:
+            B.es_destroy(h)

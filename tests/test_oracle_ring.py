@@ -210,3 +210,28 @@ def test_negative_control_permuted_ranks_change_bits():
     a = oracle.ring_order_reduce(g, A=1)
     b = oracle.ring_order_reduce(g[[1, 0, 2, 3]], A=1)
     assert not np.array_equal(bits(a), bits(b))
+
+
+def test_random_geometries_against_closed_form():
+    """Property test: the message-passing simulation equals the rotated left fold for
+    arbitrary rank counts, lengths and alignments (hypothesis draws the cases)."""
+    from hypothesis import given, settings, strategies as st
+
+    @settings(max_examples=300, deadline=None)
+    @given(N=st.integers(1, 13), L=st.integers(0, 260), A=st.sampled_from([1, 2, 3, 4, 8, 64]),
+           seed=st.integers(0, 2 ** 31 - 1))
+    def prop(N, L, A, seed):
+        g = wide_random((N, L), seed)
+        got = oracle.ring_order_reduce(g, A=A)
+        assert np.array_equal(bits(got), bits(fold_def.fold_reduce(g, A=A)))
+        # element i's fold starts at the rank that owns its chunk
+        if L:
+            cl = fold_def.chunk_len(L, N, A)
+            i = seed % L
+            c = i // cl
+            acc = np.float32(g[c % N, i])
+            for k in range(1, N):
+                acc = np.float32(acc + g[(c + k) % N, i])
+            assert bits(got[i:i + 1])[0] == bits(np.array([acc / np.float32(N)]))[0]
+
+    prop()
