@@ -255,6 +255,25 @@ int check_ctx_call(es_handle* h, uint32_t est)
 
 int aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
+// Makes the handle's device current for the duration of a call and puts the
+// caller's device back afterwards (the handle lives on the device that was
+// current at es_init).
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    explicit DeviceGuard(const es_handle* h)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != h->device)
+            switched = hipSetDevice(h->device) == hipSuccess;
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+    DeviceGuard(const DeviceGuard&) = delete;
+    DeviceGuard& operator=(const DeviceGuard&) = delete;
+};
+
 }  // namespace
 
 extern "C" {
@@ -319,6 +338,7 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
 int es_destroy(es_handle* h)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     (void)hipStreamSynchronize(h->s_main);
     (void)hipStreamSynchronize(h->s_ctx);
     (void)hipStreamSynchronize(h->s_stage);
@@ -336,6 +356,7 @@ int es_destroy(es_handle* h)
 int es_set_streams(es_handle* h, void* main, void* ctx, void* stage)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     int rc = sync_all(h);
     if (rc != ES_OK) return rc;
     h->s_main = (hipStream_t)main;
@@ -378,6 +399,7 @@ int es_set_grouping(es_handle* h, uint32_t n_workers, const uint32_t* worker_of_
                     const uint32_t* slot_of_est)
 try {
     if (!h || !worker_of_est || !slot_of_est) return ES_EINVAL;
+    DeviceGuard guard__(h);
     std::vector<uint32_t> counts;
     if (!valid_grouping(h->N, n_workers, worker_of_est, slot_of_est, counts)) return ES_EINVAL;
     if (h->n_accumulated != 0) return ES_ESTATE;
@@ -417,6 +439,7 @@ try {
 int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs)
 try {
     if (!h || worker >= h->workers.size()) return ES_EINVAL;
+    DeviceGuard guard__(h);
     const size_t ns = h->seg_bytes.size();
     if (ns && !live_ptrs) return ES_EINVAL;
     for (size_t j = 0; j < ns; ++j)
@@ -463,6 +486,7 @@ int es_ctx_restore(es_handle* h, uint32_t est)
 {
     int rc = check_ctx_call(h, est);
     if (rc != ES_OK) return rc;
+    DeviceGuard guard__(h);
     if (h->seg_bytes.empty()) return ES_OK;
     const Worker& w = h->workers[h->worker_of[est]];
     if ((rc = order_after(h, h->s_ctx, h->s_main, h->ev_main)) != ES_OK) return rc;
@@ -474,6 +498,7 @@ int es_ctx_save(es_handle* h, uint32_t est)
 {
     int rc = check_ctx_call(h, est);
     if (rc != ES_OK) return rc;
+    DeviceGuard guard__(h);
     if (h->seg_bytes.empty()) return ES_OK;
     const Worker& w = h->workers[h->worker_of[est]];
     if ((rc = order_after(h, h->s_ctx, h->s_main, h->ev_main)) != ES_OK) return rc;
@@ -484,6 +509,7 @@ int es_ctx_save(es_handle* h, uint32_t est)
 int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in)
 {
     if (!h || est_out >= h->N || est_in >= h->N || est_out == est_in) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->worker_of[est_out] != h->worker_of[est_in]) return ES_EINVAL;
     if (h->seg_bytes.empty()) return ES_OK;
     const Worker& w = h->workers[h->worker_of[est_out]];
@@ -503,6 +529,7 @@ float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket)
 int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_grad_bucket)
 {
     if (!h || est >= h->N || bucket >= h->buckets.size()) return ES_EINVAL;
+    DeviceGuard guard__(h);
     const uint64_t len = h->buckets[bucket].len_elems;
     if (len && (!d_grad_bucket || (((uintptr_t)d_grad_bucket) & 3))) return ES_EINVAL;
     uint8_t& flag = h->accumulated[(size_t)est * h->buckets.size() + bucket];
@@ -526,6 +553,7 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
                         const float* const* d_grad_buckets)
 {
     if (!h || est >= h->N || (n && (!buckets || !d_grad_buckets))) return ES_EINVAL;
+    DeviceGuard guard__(h);
     const size_t nb = h->buckets.size();
     // validate everything first: a failing call must enqueue nothing and mark nothing
     for (uint32_t k = 0; k < n; ++k) {
@@ -616,6 +644,7 @@ int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad)
 int es_stage_fence(es_handle* h)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (!h->stage_pending) return ES_OK;
     int rc = order_after(h, h->s_main, h->s_stage, h->ev_stage);
     if (rc == ES_OK) h->stage_pending = false;
@@ -626,6 +655,7 @@ int es_dropout_mask(es_handle* h, uint32_t est, uint32_t state_seg, uint8_t* d_m
                     double p)
 {
     if (!h || est >= h->N || state_seg >= h->seg_bytes.size()) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->seg_bytes[state_seg] != 16 || (n && !d_mask) || !(p >= 0.0 && p <= 1.0)) return ES_EINVAL;
     const Worker& w = h->workers[h->worker_of[est]];
     if (!w.bound) return ES_ESTATE;
@@ -664,6 +694,7 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
 int es_ring_order_reduce(es_handle* h, float* d_avg_grad)
 {
     if (!h || (h->P && (!d_avg_grad || !aligned16(d_avg_grad)))) return ES_EINVAL;
+    DeviceGuard guard__(h);
     return reduce_common(h, d_avg_grad, nullptr, nullptr, 0.f, 0.f);
 }
 
@@ -671,6 +702,7 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_
                 float lr, float mu)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum || !d_avg_grad)) return ES_EINVAL;
     if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
     ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu));
@@ -680,6 +712,7 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_
 int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2)
 {
     if (!h || !d_out2 || (((uintptr_t)d_out2) & 3)) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->P && (!d_vec || !aligned16(d_vec))) return ES_EINVAL;
     ES_HIP(h, launch_sq_norm(h->s_main, d_vec, h->P, h->d_partials, d_out2));
     return ES_OK;
@@ -689,6 +722,7 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum, float* d
                        float lr, float mu)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
     if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
     return reduce_common(h, d_avg_grad, d_param, d_momentum, lr, mu);
@@ -711,6 +745,7 @@ int es_checkpoint_export(es_handle* h, void* host_blob, uint64_t capacity, const
                          const float* d_momentum, uint64_t global_step)
 {
     if (!h || !host_blob || capacity < ckpt_bytes(h)) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
     if (h->n_accumulated != 0) return ES_ESTATE;
     int rc = sync_all(h);
@@ -739,6 +774,7 @@ int es_checkpoint_import(es_handle* h, const void* host_blob, uint64_t size, flo
                          float* d_momentum, uint64_t* global_step)
 {
     if (!h || !host_blob || size != ckpt_bytes(h)) return ES_EINVAL;
+    DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
     const uint8_t* in = (const uint8_t*)host_blob;
     uint64_t hdr[8];
@@ -772,12 +808,14 @@ int es_checkpoint_import(es_handle* h, const void* host_blob, uint64_t size, flo
 int es_sync(es_handle* h)
 {
     if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
     return sync_all(h);
 }
 
 int es_set_option(es_handle* h, const char* name, int64_t value)
 try {
     if (!h || !name) return ES_EINVAL;
+    DeviceGuard guard__(h);
     const std::string k(name);
     if (k == "reduce_tile_elems") {
         if (value < 256 || value > 65536 || (value & 3)) return ES_EINVAL;
