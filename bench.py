@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--overlap-demo", action="store_true",
                     help="separate experiment: staging on its own stream overlapped with a compute-bound "
                          "stand-in for the next EST's forward/backward (prints its own JSON line)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="separate experiment: what this box's HBM gives the library's plain copy and "
+                         "pure-read kernels on 1 GiB (prints its own JSON line)")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
     return ap.parse_args()
 
@@ -149,8 +152,61 @@ def overlap_demo(a):
     print(json.dumps(out))
 
 
+def ceilings(a):
+    """Plain streaming rates on this machine, measured with the library's own kernels: the staging
+    copy (k_copy_f4, read + write) and the norm's first stage (k_sq_partials, read only) on a
+    1 GiB vector.  Context for the roofline fractions; the vendor peak stays the denominator."""
+    import torch
+
+    from paper_2208_14228_amd import binding as B
+    from paper_2208_14228_amd.job import ESTJob
+
+    P = 1 << 28
+    job = ESTJob(1, P, [(0, P)], 4, use_streams="one")
+    src = torch.ones(P, device="cuda:0")
+    out2 = torch.zeros(2, device="cuda:0")
+    slot = B.es_grad_slot(job.h, 0, 0)
+
+    def timed(fn, reps=10):
+        for _ in range(3):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(job.main)
+        for _ in range(reps):
+            fn()
+        e1.record(job.main)
+        job.sync(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    def copy():
+        B.es_accumulate(job.h, 0, 0, src.data_ptr())
+        job.ring_order_reduce()    # N = 1: ends the step so the bucket can be staged again
+
+    # the N = 1 reduce is itself a 1 GiB copy (read slot, write avg): time it alone and subtract
+    B.es_accumulate(job.h, 0, 0, src.data_ptr()); job.ring_order_reduce(); job.sync()
+
+    def reduce_only():
+        B.es_accumulate(job.h, 0, 0, slot)
+        job.ring_order_reduce()
+
+    t_both, t_red = timed(copy), timed(reduce_only)
+    t_norm = timed(lambda: B.es_grad_sq_norm(job.h, src.data_ptr(), out2.data_ptr()))
+    gb = 4 * P / 1e9
+    res = {"experiment": "plain streaming rates of the library's kernels on 1 GiB",
+           "copy_read_plus_write_GBps": round(2 * gb / ((t_both - t_red) * 1e-3), 1),
+           "n1_reduce_read_plus_write_GBps": round(2 * gb / (t_red * 1e-3), 1),
+           "norm_read_only_pass_GBps": round(gb / (t_norm * 1e-3), 1), "hbm_peak_GBps": HBM_PEAK_GBPS}
+    job.close()
+    print(json.dumps(res))
+
+
 def main():
     a = parse()
+    if a.ceilings:
+        if a.gpus != 1:
+            sys.exit(2)
+        ceilings(a)
+        return
     if a.overlap_demo:
         if a.gpus != 1:
             sys.exit(2)
