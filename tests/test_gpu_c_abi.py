@@ -21,7 +21,7 @@ def build_c_abi_program(force=False) -> str:
             "-I", "/opt/rocm/include", src, os.path.join(ROOT, "oracle", "es_oracle.c"),
             "-ffp-contract=off", "-o", EXE,
             "-L", pkg, "-l:libes.so", "-L", "/opt/rocm/lib", "-lamdhip64",
-            "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib"])
+            "-Wl,-rpath,$ORIGIN/../../paper_2208_14228_amd", "-Wl,-rpath,/opt/rocm/lib"])
     return EXE
 
 
