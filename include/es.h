@@ -301,6 +301,11 @@ int es_sync(es_handle* h);
  *                         per-EST gradients in host memory, section 3.2; here it is the
  *                         memory-pressure mode for N * n_params beyond HBM): staging and
  *                         reduce run unchanged and reach the gradients over the host link
+ *   "hbm_slot_budget_mib" -1 (no limit, default) or >= 0: at the NEXT es_set_grouping the
+ *                         workers' gradient arenas are placed in HBM in worker order until
+ *                         this many MiB are used; the arenas that no longer fit spill to
+ *                         pinned host memory (only what does not fit pays the host link)
+ *   "slots_on_host"       read-only (es_get_option): ESTs whose gradient slot is on the host
  *   "reduce_tile_elems"   elements of one bucket chunk handled by one workgroup
  *                         (multiple of 4, 256 .. 65536)
  *   "reduce_unroll"       16-byte vectors per lane in flight per rank (1, 2, 4)

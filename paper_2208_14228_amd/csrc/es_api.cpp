@@ -62,6 +62,8 @@ struct es_handle {
 
     // one pass per workgroup: 256 lanes x 2 vectors x 4 floats (measured best on MI355X)
     bool host_slots = false;                    // where the next arena allocation places gradient slots
+    int64_t hbm_budget_mib = -1;                // >= 0: gradient arenas beyond this many MiB of HBM go to the host
+    uint64_t hbm_grad_bytes = 0;                // HBM held by gradient arenas allocated in the current regrouping
     uint32_t tile_elems = 2048;
     ReduceShape shape{2, 8, 1, 0, 1, 0};
 
@@ -112,7 +114,9 @@ int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
     if (gbytes) {
         // host placement: pinned, device-mapped memory; the staging copy and the reduce then
         // reach the gradients over the host link with the same kernels (memory-pressure mode)
-        w.grad_on_host = h->host_slots;
+        w.grad_on_host = h->host_slots ||
+                         (h->hbm_budget_mib >= 0 && h->hbm_grad_bytes + gbytes > ((uint64_t)h->hbm_budget_mib << 20));
+        if (!w.grad_on_host) h->hbm_grad_bytes += gbytes;
         hipError_t e = w.grad_on_host
                            ? hipHostMalloc((void**)&w.grad_arena, gbytes, hipHostMallocMapped | hipHostMallocPortable)
                            : hipMalloc((void**)&w.grad_arena, gbytes);
@@ -407,6 +411,7 @@ try {
     if (rc != ES_OK) return rc;
 
     std::vector<Worker> fresh(n_workers);
+    h->hbm_grad_bytes = 0;                       // placement is decided anew, worker by worker
     for (uint32_t w = 0; w < n_workers && rc == ES_OK; ++w) {
         fresh[w].live.assign(h->seg_bytes.size(), nullptr);
         rc = alloc_worker(h, fresh[w], counts[w]);
@@ -861,6 +866,11 @@ try {
         h->host_slots = value != 0;
         return ES_OK;
     }
+    if (k == "hbm_slot_budget_mib") {
+        if (value < -1) return ES_EINVAL;
+        h->hbm_budget_mib = value;
+        return ES_OK;
+    }
     if (k == "nontemporal_pv") {
         if (value != 0 && value != 1) return ES_EINVAL;
         h->shape.nontemporal_pv = (int)value;
@@ -881,6 +891,12 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "nontemporal") *value = h->shape.nontemporal;
     else if (k == "nontemporal_pv") *value = h->shape.nontemporal_pv;
     else if (k == "host_slots") *value = h->host_slots ? 1 : 0;
+    else if (k == "hbm_slot_budget_mib") *value = h->hbm_budget_mib;
+    else if (k == "slots_on_host") {             // read-only: ESTs whose gradient slot is in host memory now
+        int64_t n = 0;
+        for (uint32_t e = 0; e < h->N; ++e) n += h->workers[h->worker_of[e]].grad_on_host ? 1 : 0;
+        *value = n;
+    }
     else if (k == "reduce_big_unroll") *value = h->shape.big_unroll;
     else if (k == "reduce_big_rank_batch") *value = h->shape.big_rank_batch;
     else return ES_EINVAL;

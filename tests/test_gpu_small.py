@@ -533,3 +533,27 @@ def test_degenerate_layouts():
             assert B.es_checkpoint_import(h, blob.ctypes.data, n, 0, 0) == (B.ES_OK, 3)
         finally:
             B.es_destroy(h)
+
+
+def test_spilling_some_arenas_to_host_keeps_the_bits():
+    """HBM budget for gradient slots: workers that no longer fit get host-resident arenas."""
+    N = 6
+    sc = S.Scenario(N, buckets.custom([300000, 0, 7, 100001], fan_in=5), 4, 93, steps=2)
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([2, 2, 2])
+    job = G.make_job(sc, configs.contiguous([N]))
+    try:
+        per_worker_mib = 2 * sc.layout.n_params * 4 / 2 ** 20
+        job.set_option("hbm_slot_budget_mib", int(per_worker_mib * 2) + 1)      # room for two of three arenas
+        job.set_grouping(g.worker_of_est, g.slot_of_est)
+        assert B.es_get_option(job.h, "slots_on_host") == (0, 2)
+        G.init_contexts(sc, job)
+        G.run_steps(sc, job, g, fused=True)
+        for name, got, want in (("avg", job.avg, ref.avg), ("p", job.p, ref.p), ("v", job.v, ref.v)):
+            assert np.array_equal(bits(got.cpu().numpy()), bits(want)), name
+        job.set_option("hbm_slot_budget_mib", -1)
+        job.set_grouping(g.worker_of_est, g.slot_of_est)
+        assert B.es_get_option(job.h, "slots_on_host") == (0, 0)
+        assert B.es_set_option(job.h, "hbm_slot_budget_mib", -2) == B.ES_EINVAL
+    finally:
+        job.close()
