@@ -382,12 +382,18 @@ static hipError_t launch_reduce_big_u(hipStream_t s, const Tile* tiles, uint32_t
                                       float* v, float lr, float mu, ReduceShape sh)
 {
     const int nt = (sh.nontemporal ? 1 : 0) | (sh.nontemporal_pv ? 2 : 0);
-    switch (sh.big_rank_batch) {
-    case 1: return launch_reduce_big<UB, 1>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
-    case 2: return launch_reduce_big<UB, 2>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
-    case 4: return launch_reduce_big<UB, 4>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
-    default: return hipErrorInvalidValue;
+    // only shapes whose loads in flight fit the register file exist: UB * batch <= 32
+    if (sh.big_rank_batch == 1)
+        return launch_reduce_big<UB, 1>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
+    if constexpr (UB <= 16) {
+        if (sh.big_rank_batch == 2)
+            return launch_reduce_big<UB, 2>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
     }
+    if constexpr (UB <= 8) {
+        if (sh.big_rank_batch == 4)
+            return launch_reduce_big<UB, 4>(s, tiles, n_tiles, n_big, slots, N, avg, p, v, lr, mu, nt);
+    }
+    return hipErrorInvalidValue;
 }
 
 hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles, uint32_t n_big,
