@@ -92,7 +92,9 @@ def init_contexts(sc: S.Scenario, job: ESTJob) -> None:
 
 def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=False,
               sync_each_est=False, masks: Optional[Dict] = None, mask_check=None,
-              steps: Optional[Sequence[int]] = None) -> None:
+              steps: Optional[Sequence[int]] = None, batched=False, store_avg=True) -> None:
+    """``batched``: one flat gradient vector per EST handed over with es_accumulate_batch (what
+    bench.py times) instead of one tensor and one es_accumulate per bucket."""
     mask = torch.empty(sc.mask_n, dtype=torch.uint8, device=DEV) if sc.mask_n else None
     sched = g.schedule()
     for t in (range(sc.steps) if steps is None else steps):
@@ -114,10 +116,18 @@ def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=
             if sc.bn_len:
                 bn_add_live(sc, job, e, S.bn_delta(sc, t, e, DEV))
             with job.stream_ctx():
-                for b in range(sc.layout.n_buckets):
-                    gr = S.grad(sc, t, e, b, DEV)
-                    keep.append(gr)
-                    job.accumulate(e, b, gr)
+                if batched:
+                    flat = torch.empty(sc.layout.n_params, dtype=torch.float32, device=DEV)
+                    for b, (off, ln) in enumerate(sc.layout.buckets):
+                        synth.gradient(sc.layout, b, sc.seed, t, e, DEV, out=flat[off:off + ln])
+                    keep.append(flat)
+                    job.accumulate_batch(e, list(range(sc.layout.n_buckets)),
+                                         [flat[off:off + ln] for off, ln in sc.layout.buckets])
+                else:
+                    for b in range(sc.layout.n_buckets):
+                        gr = S.grad(sc, t, e, b, DEV)
+                        keep.append(gr)
+                        job.accumulate(e, b, gr)
             if not use_switch:
                 job.ctx_save(e)
             if sync_each_est:
@@ -127,7 +137,7 @@ def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=
         if use_switch:
             job.ctx_save(sched[-1])
         if fused:
-            job.reduce_sgd_step(sc.lr, sc.momentum)
+            job.reduce_sgd_step(sc.lr, sc.momentum, store_avg=store_avg)
         else:
             job.ring_order_reduce()
             job.sgd_step(sc.lr, sc.momentum)

@@ -41,6 +41,24 @@ def test_full_replay(cid):
     for gi, g in enumerate(cfg.groupings):
         got = G.run_gpu(sc, g, fused=bool(gi % 2), use_switch=bool(gi % 2))
         S.assert_same(got, ref, f"config {cid} grouping {g.name}")
+    bench_launch_configuration(sc, cfg.groupings[0], ref.p, ref.v)
+
+
+def bench_launch_configuration(sc, g, want_p, want_v):
+    """Exactly what bench.py times: one in-order stream, one flat gradient vector per EST
+    staged by es_accumulate_batch, fused switch, fused reduce+update without storing the average."""
+    job = G.make_job(sc, g, use_streams="one")
+    try:
+        G.init_contexts(sc, job)
+        G.run_steps(sc, job, g, fused=True, use_switch=True, batched=True, store_avg=False,
+                    sync_each_est=sc.layout.n_params * sc.n_logical > (1 << 31))
+        if isinstance(want_p, np.ndarray):
+            assert np.array_equal(bits(job.p.cpu().numpy()), bits(want_p)), "bench configuration: parameters"
+            assert np.array_equal(bits(job.v.cpu().numpy()), bits(want_v)), "bench configuration: momentum"
+        else:                                   # device tensors of another run of the same job
+            assert dev_bits_equal(job.p, want_p) and dev_bits_equal(job.v, want_v), "bench configuration"
+    finally:
+        job.close()
 
 
 def windows_for(sc: S.Scenario, n_random: int, seed: int) -> List[Tuple[int, int, int]]:
@@ -141,6 +159,8 @@ def run_sampled(cid: int, steps: int, n_random: int, whole_buckets, sync_each_es
                 got = G.collect(sc, job, masks)
                 assert np.array_equal(got.philox, want_philox), what
             cur = (job.avg.clone(), job.p.clone(), job.v.clone())
+            if gi == 0:
+                p_first, v_first = cur[1], cur[2]
             if keep is None:
                 keep = cur
             else:                       # groupings agree over the whole vectors
@@ -149,6 +169,9 @@ def run_sampled(cid: int, steps: int, n_random: int, whole_buckets, sync_each_es
         finally:
             job.close()
         torch.cuda.empty_cache()
+    # the windows and whole buckets above pin the first run to the oracle; the launch
+    # configuration bench.py times has to reproduce that run over the whole vectors
+    bench_launch_configuration(sc, cfg.groupings[0], p_first, v_first)
 
 
 def test_config3_bert_base_with_philox_context():
