@@ -62,7 +62,7 @@ typedef struct es_bucket {
  * The recorded gradient-bucket mapping (paper §3.3: the mapping is stored and
  * reinstated, never rebuilt) and the shape of the small per-EST state.
  *   buckets          HOST array; ranges must be disjoint, ascending and cover
- *                    [0, n_params) exactly.  Copied by es_init.
+ *                    [0, n_params) exactly (n_params <= 2^40).  Copied by es_init.
  *   chunk_align      >= 1.  Each bucket of length L is cut into n_logical ring
  *                    chunks of length roundup(ceil(L / n_logical), chunk_align);
  *                    trailing chunks may be short or empty.  4 keeps every
@@ -120,6 +120,9 @@ int es_set_streams(es_handle* h, void* main, void* ctx, void* stage);
  * ESTs are carried over to their new slots (device copies); staged gradients
  * are not, so this must be called between global steps (ES_ESTATE otherwise).
  * Live-state bindings are dropped.  Synchronises the handle's streams.
+ * The new arenas are allocated before the old ones are freed, so a call that
+ * fails (ES_ENOMEM, ES_EHIP) leaves the previous grouping fully usable; the
+ * price is that both sets of gradient slots exist for the duration of the call.
  */
 int es_set_grouping(es_handle* h, uint32_t n_workers,
                     const uint32_t* worker_of_est, const uint32_t* slot_of_est);

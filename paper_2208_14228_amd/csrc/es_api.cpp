@@ -194,7 +194,7 @@ int validate_layout(uint32_t n_logical, const es_bucket_layout* lay)
         if (lay->buckets[b].len_elems > (1ull << 40)) return ES_EINVAL;
         pos += lay->buckets[b].len_elems;
     }
-    if (pos != lay->n_params) return ES_EINVAL;
+    if (pos != lay->n_params || pos > (1ull << 40)) return ES_EINVAL;
     for (uint32_t j = 0; j < lay->n_state_segs; ++j)
         if (lay->state_seg_bytes[j] == 0 || lay->state_seg_bytes[j] > (1ull << 32)) return ES_EINVAL;
     return ES_OK;
@@ -685,11 +685,14 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     }
     // gradients taken in place: point their ranks at caller memory for this launch only
     ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
-    ES_HIP(h, launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N, avg, p, v, lr, mu, h->shape));
-    if (h->in_place.n) {
+    const hipError_t launched = launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N,
+                                                   avg, p, v, lr, mu, h->shape);
+    if (h->in_place.n) {                         // the table goes back to the slots whether or not the launch worked
         for (uint32_t k = 0; k < h->in_place.n; ++k) h->in_place.ptr[k] = slot_base(h, h->in_place.rank[k]);
-        ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
+        const hipError_t restored = launch_patch_slots(h->s_main, h->d_slots, h->in_place);
+        if (launched == hipSuccess) ES_HIP(h, restored);
     }
+    ES_HIP(h, launched);
     std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
     h->n_accumulated = 0;
     h->in_place.n = 0;
