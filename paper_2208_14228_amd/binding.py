@@ -35,6 +35,19 @@ class EsTile(ctypes.Structure):
                 ("start_rank", ctypes.c_uint32)]
 
 
+ES_SCHED_MAX_TYPES, ES_SCHED_MAX_P = 8, 4096
+ES_SCHED_WASTE_PER_GPU, ES_SCHED_WASTE_AS_PRINTED = 0, 1
+
+
+class EsSchedPlan(ctypes.Structure):
+    """es_sched_plan of include/es_sched.h."""
+    _fields_ = [("n_used", ctypes.c_uint32 * ES_SCHED_MAX_TYPES),
+                ("est_per_gpu", ctypes.c_uint32 * ES_SCHED_MAX_TYPES),
+                ("n_gpus", ctypes.c_uint32), ("n_est", ctypes.c_uint32),
+                ("f_overload", ctypes.c_double), ("waste", ctypes.c_double),
+                ("throughput", ctypes.c_double)]
+
+
 class EsError(RuntimeError):
     def __init__(self, status: int, where: str, hip: int = 0):
         self.status = status
@@ -84,6 +97,19 @@ _SIGS = {
     "es_last_hip_error": (ctypes.c_int, [_VP]),
     "es_strerror": (ctypes.c_char_p, [ctypes.c_int]),
     "es_version": (ctypes.c_char_p, []),
+    # include/es_sched.h
+    "es_sched_evaluate": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(ctypes.c_double),
+                                         ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32),
+                                         ctypes.c_uint32, ctypes.c_int, ctypes.POINTER(EsSchedPlan)]),
+    "es_sched_best_mapping": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(ctypes.c_double),
+                                             ctypes.POINTER(ctypes.c_uint32), ctypes.c_uint32,
+                                             ctypes.POINTER(EsSchedPlan)]),
+    "es_sched_enumerate": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(ctypes.c_double),
+                                          ctypes.POINTER(ctypes.c_uint32), ctypes.c_uint32, ctypes.c_uint32,
+                                          ctypes.POINTER(EsSchedPlan), ctypes.POINTER(ctypes.c_uint32)]),
+    "es_sched_grouping": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(EsSchedPlan), ctypes.c_uint32,
+                                         ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(ctypes.c_uint32),
+                                         ctypes.POINTER(ctypes.c_uint32)]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -235,3 +261,52 @@ def es_query(h):
 def es_last_hip_error(h): return lib().es_last_hip_error(h)
 def es_strerror(status): return lib().es_strerror(status).decode()
 def es_version(): return lib().es_version().decode()
+
+
+# ---- include/es_sched.h: host-only planning ------------------------------------------
+
+def _dbl(xs): return (ctypes.c_double * max(1, len(xs)))(*[float(x) for x in xs])
+def _u32(xs): return (ctypes.c_uint32 * max(1, len(xs)))(*[int(x) for x in xs])
+
+
+def _plan_dict(p: EsSchedPlan, n_types: int) -> dict:
+    return dict(n_used=tuple(p.n_used[:n_types]), est_per_gpu=tuple(p.est_per_gpu[:n_types]),
+                n_gpus=p.n_gpus, n_est=p.n_est, f_overload=p.f_overload, waste=p.waste,
+                throughput=p.throughput)
+
+
+def es_sched_evaluate(capability, n_used, est_per_gpu, max_p: int, waste_reading: int = ES_SCHED_WASTE_PER_GPU):
+    """Returns (status, plan dict or None)."""
+    out = EsSchedPlan()
+    st = lib().es_sched_evaluate(len(capability), _dbl(capability), _u32(n_used), _u32(est_per_gpu),
+                                 max_p, waste_reading, ctypes.byref(out))
+    return st, (_plan_dict(out, len(capability)) if st == ES_OK else None)
+
+
+def es_sched_best_mapping(capability, n_used, max_p: int):
+    """Returns (status, plan dict or None)."""
+    out = EsSchedPlan()
+    st = lib().es_sched_best_mapping(len(capability), _dbl(capability), _u32(n_used), max_p, ctypes.byref(out))
+    return st, (_plan_dict(out, len(capability)) if st == ES_OK else None)
+
+
+def es_sched_enumerate(capability, available, max_p: int, top_k: int):
+    """Returns (status, [plan dict, ...])."""
+    out = (EsSchedPlan * max(1, top_k))()
+    n = ctypes.c_uint32()
+    st = lib().es_sched_enumerate(len(capability), _dbl(capability), _u32(available), max_p, top_k,
+                                  out, ctypes.byref(n))
+    return st, ([_plan_dict(out[k], len(capability)) for k in range(n.value)] if st == ES_OK else [])
+
+
+def es_sched_grouping(n_used, est_per_gpu, max_p: int):
+    """Returns (status, n_workers, worker_of_est, slot_of_est)."""
+    plan = EsSchedPlan()
+    for i, (n, a) in enumerate(zip(n_used, est_per_gpu)):
+        plan.n_used[i], plan.est_per_gpu[i] = int(n), int(a)
+    wo, so = (ctypes.c_uint32 * max(1, max_p))(), (ctypes.c_uint32 * max(1, max_p))()
+    nw = ctypes.c_uint32()
+    st = lib().es_sched_grouping(len(n_used), ctypes.byref(plan), max_p, wo, so, ctypes.byref(nw))
+    if st != ES_OK:
+        return st, 0, [], []
+    return st, nw.value, list(wo[:max_p]), list(so[:max_p])

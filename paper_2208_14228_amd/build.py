@@ -9,8 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libes.so")
-SOURCES = [os.path.join(CSRC, "es_kernels.hip"), os.path.join(CSRC, "es_api.cpp")]
-HEADERS = [os.path.join(CSRC, "es_internal.h"), os.path.join(ROOT, "include", "es.h")]
+SOURCES = [os.path.join(CSRC, "es_kernels.hip"), os.path.join(CSRC, "es_api.cpp"),
+           os.path.join(CSRC, "es_sched.cpp")]
+HEADERS = [os.path.join(CSRC, "es_internal.h"), os.path.join(ROOT, "include", "es.h"),
+           os.path.join(ROOT, "include", "es_sched.h")]
 
 # -ffp-contract=off: no fused multiply-add may be formed (bit-exact SGD update)
 # -fhip-fp32-correctly-rounded-divide-sqrt: IEEE division for the /N

@@ -7,6 +7,7 @@
 
 #include "es.h"
 #include "es_internal.h"
+#include "es_sched.h"
 
 namespace es {
 hipError_t launch_ring_reduce(hipStream_t, const Tile*, uint32_t, uint32_t, const float* const*, uint32_t,
@@ -61,6 +62,29 @@ int main()
     if (h) CHECK(es_destroy(h) == ES_OK);
     CHECK(es_sync(nullptr) == ES_EINVAL && es_destroy(nullptr) == ES_EINVAL);
     CHECK(es_checkpoint_bytes(nullptr) == 0);
+    // scheduler-side planner: bit-set edges, clipped caps, ranking buffer of every size
+    unsigned searched = 0;
+    const double C[3] = {9.5, 4.25, 0.75};
+    for (uint32_t max_p : {1u, 2u, 63u, 64u, 65u, 129u, 1000u, (unsigned)ES_SCHED_MAX_P})
+        for (uint32_t top_k : {1u, 2u, 7u, 64u}) {
+            const uint32_t avail[3] = {3, 2, 2};
+            std::vector<es_sched_plan> plans(top_k);
+            uint32_t n = 0;
+            CHECK(es_sched_enumerate(3, C, avail, max_p, top_k, plans.data(), &n) == ES_OK && n <= top_k);
+            for (uint32_t k = 0; k < n; ++k) {
+                CHECK(plans[k].n_est >= max_p && plans[k].n_gpus >= 1 && plans[k].n_gpus <= max_p);
+                std::vector<uint32_t> wo(max_p), so(max_p);
+                uint32_t nw = 0;
+                CHECK(es_sched_grouping(3, &plans[k], max_p, wo.data(), so.data(), &nw) == ES_OK);
+                CHECK(nw == plans[k].n_gpus && wo[max_p - 1] == nw - 1);
+                es_sched_plan again;
+                CHECK(es_sched_evaluate(3, C, plans[k].n_used, plans[k].est_per_gpu, max_p,
+                                        ES_SCHED_WASTE_PER_GPU, &again) == ES_OK);
+                CHECK(again.throughput == plans[k].throughput && again.n_est == plans[k].n_est);
+                ++searched;
+            }
+        }
+    CHECK(searched > 0);
     std::printf("host runtime sanitizer run: %u plans clean\n", planned);
     return 0;
 }

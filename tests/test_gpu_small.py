@@ -557,3 +557,16 @@ def test_spilling_some_arenas_to_host_keeps_the_bits():
         assert B.es_set_option(job.h, "hbm_slot_budget_mib", -2) == B.ES_EINVAL
     finally:
         job.close()
+
+
+def test_grouping_from_a_scheduler_plan():
+    """Paper section 3.4 feeding section 3.2: the best plan for three GPU types becomes the
+    EST-to-worker grouping of the step; the bits stay those of 9-worker data parallelism."""
+    st, plans = B.es_sched_enumerate([8.0, 4.0, 2.0], [1, 1, 2], 9, top_k=1)
+    assert st == B.ES_OK and len(plans) == 1
+    st, nw, wo, so = B.es_sched_grouping(plans[0]["n_used"], plans[0]["est_per_gpu"], 9)
+    assert st == B.ES_OK and nw == plans[0]["n_gpus"] >= 2
+    g = configs.Grouping("plan", tuple(wo), tuple(so))
+    sc = ragged_scenario(9, 1, 91, steps=2, mask_n=77, bn_channels=(4, 9))
+    ref = S.run_ddp_reference(sc)
+    S.assert_same(G.run_gpu(sc, g, fused=True, use_switch=True), ref, "grouping of the best plan")

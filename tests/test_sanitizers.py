@@ -25,13 +25,14 @@ def test_oracle_is_clean_under_asan_ubsan(tmp_path):
 
 
 def test_host_runtime_is_clean_under_asan_ubsan(tmp_path):
-    """libes' host logic (layout validation, tile planning, argument checks) with the kernel
+    """libes' host logic (layout validation, tile planning, argument checks, plan search) with the kernel
     launchers stubbed out: host code only, no device code is built or run."""
     exe = str(tmp_path / "host_san")
     pkg = os.path.join(ROOT, "paper_2208_14228_amd", "csrc")
     cmd = ["g++", "-O1", "-g", "-std=c++17", "-D__HIP_PLATFORM_AMD__", "-fsanitize=address,undefined",
            "-fno-sanitize-recover=all", "-I", os.path.join(ROOT, "include"), "-I", pkg, "-I", "/opt/rocm/include",
            os.path.join(HERE, "c_abi", "host_san.cpp"), os.path.join(pkg, "es_api.cpp"),
+           os.path.join(pkg, "es_sched.cpp"),
            "-o", exe, "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib"]
     try:
         subprocess.check_call(cmd, stderr=subprocess.STDOUT)
