@@ -570,3 +570,49 @@ def test_grouping_from_a_scheduler_plan():
     sc = ragged_scenario(9, 1, 91, steps=2, mask_n=77, bn_channels=(4, 9))
     ref = S.run_ddp_reference(sc)
     S.assert_same(G.run_gpu(sc, g, fused=True, use_switch=True), ref, "grouping of the best plan")
+
+
+def test_random_layouts_groupings_and_launch_shapes():
+    """Seeded sweep: bucket lengths around tile, chunk and vector boundaries, any N and chunk
+    alignment, random EST-to-worker groupings and launch shapes; every case bit-exact."""
+    rng = np.random.default_rng(20240607)
+    for case in range(36):
+        N = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 12, 16, 17, 24, 32, 40]))
+        A = int(rng.choice([1, 1, 2, 4, 4, 8, 64]))
+        tile = int(rng.choice([256, 512, 2048, 2048, 8192]))
+        lens = []
+        for _ in range(int(rng.integers(1, 6))):
+            kind = int(rng.integers(0, 6))
+            if kind == 0:
+                lens.append(int(rng.integers(0, 4)))
+            elif kind == 1:
+                lens.append(int(rng.integers(1, 3 * N + 6)))
+            elif kind == 2:                                   # around a multiple of tile * N
+                lens.append(max(0, tile * N * int(rng.integers(1, 3)) + int(rng.integers(-5, 6))))
+            elif kind == 3:                                   # around a multiple of the tile
+                lens.append(max(0, tile * int(rng.integers(1, 9)) + int(rng.integers(-5, 6))))
+            elif kind == 4:                                   # long enough for big tiles when N is small
+                lens.append(N * 8192 * int(rng.integers(1, 3)) + int(rng.integers(0, 4099)))
+            else:
+                lens.append(int(rng.integers(1, 60000)))
+        # a random grouping: worker sizes, then one of the three placements
+        sizes, left = [], N
+        while left:
+            k = int(rng.integers(1, left + 1))
+            sizes.append(k)
+            left -= k
+        g = (configs.contiguous, configs.round_robin,
+             lambda s: configs.reversed_slots(configs.contiguous(s)))[int(rng.integers(0, 3))](sizes)
+        options = {"reduce_tile_elems": tile, "reduce_unroll": int(rng.choice([1, 2, 4])),
+                   "reduce_rank_batch": int(rng.choice([1, 2, 4, 8, 16])),
+                   "nontemporal": int(rng.integers(0, 2)), "nontemporal_pv": int(rng.integers(0, 2)),
+                   "reduce_big_unroll": int(rng.choice([0, 0, 8, 16, 32]))}
+        fused, switch = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        streams = [True, "two", "one", False][int(rng.integers(0, 4))]
+        what = f"case {case}: N={N} A={A} lens={lens} grouping={g.name} {options} fused={fused} streams={streams}"
+        print("[gpu-case]", what, flush=True)
+        sc = S.Scenario(N, buckets.custom(lens, fan_in=5), A, 9000 + case, steps=2,
+                        mask_n=int(rng.integers(0, 300)), bn_channels=(3, int(rng.integers(1, 70))))
+        ref = S.run_ddp_reference(sc)
+        S.assert_same(G.run_gpu(sc, g, fused=fused, use_switch=switch, use_streams=streams, options=options),
+                      ref, what)
