@@ -465,6 +465,25 @@ def main():
     job.sync(); torch.cuda.synchronize()
     norm_ms = n0.elapsed_time(n1) / a.steps
 
+    # on-demand checkpoint (all EST contexts by virtual rank + one copy of p and v) to a pinned
+    # host blob and back: host-link traffic, timed on the wall clock (the calls are synchronous)
+    ck_n = B.es_checkpoint_bytes(job.h)
+    blob = torch.empty(ck_n, dtype=torch.uint8, pin_memory=True)
+    ck_ms = {}
+    for name in ("export", "import"):
+        best = None
+        for _ in range(3):
+            t0 = time.perf_counter()
+            if name == "export":
+                B.check(B.es_checkpoint_export(job.h, blob.data_ptr(), ck_n, job.p.data_ptr(), job.v.data_ptr(), 1),
+                        "es_checkpoint_export", job.h)
+            else:
+                B.check(B.es_checkpoint_import(job.h, blob.data_ptr(), ck_n, job.p.data_ptr(), job.v.data_ptr())[0],
+                        "es_checkpoint_import", job.h)
+            t = (time.perf_counter() - t0) * 1e3
+            best = t if best is None else min(best, t)
+        ck_ms[name] = best
+
     ctx_bytes = sum(segs)
     bytes_stage = 2 * N * 4 * P
     bytes_reduce = (N + 4) * 4 * P if fused else (N + 1) * 4 * P
@@ -522,6 +541,11 @@ def main():
                          "avg_ms": round(norm_ms, 4),
                          "achieved": round(4 * P / (norm_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                          "frac": round(4 * P / (norm_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "checkpoint": {"note": "es_checkpoint_export / es_checkpoint_import to and from a pinned host blob "
+                               "(host link, not HBM; best of 3)", "bytes": ck_n,
+                       "export_ms": round(ck_ms["export"], 3), "import_ms": round(ck_ms["import"], 3),
+                       "export_GBps": round(ck_n / (ck_ms["export"] * 1e-3) / 1e9, 1),
+                       "import_GBps": round(ck_n / (ck_ms["import"] * 1e-3) / 1e9, 1)},
         "cold_step": None if cold_ms is None else {
             "note": "working set fits the Infinity Cache: step timed after a 1 GiB cache sweep",
             "ms_per_step": round(cold_ms, 4), "value": round(total / (cold_ms * 1e-3) / 1e9, 2), "unit": "GB/s"},
