@@ -232,7 +232,8 @@ int es_ring_order_reduce(es_handle* h, float* d_avg_grad);
  * SGD with momentum on the single shared replica (paper §3.2):
  *     v <- mu*v + g ;  p <- p - lr*v
  * every multiply and add rounded to fp32 on its own (no fused multiply-add).
- * All DEVICE, n_params floats, 16-byte aligned; p and v updated in place.
+ * All DEVICE, n_params floats, 16-byte aligned; p and v updated in place.  The
+ * three buffers must not overlap one another (ES_EINVAL).
  */
 int es_sgd_step(es_handle* h, float* d_param, float* d_momentum,
                 const float* d_avg_grad, float lr, float mu);
@@ -240,7 +241,8 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum,
 /*
  * es_ring_order_reduce and es_sgd_step in one kernel: same bits, without the
  * round trip of the averaged gradient through HBM.  d_avg_grad may be NULL
- * (not stored) or a DEVICE buffer of n_params floats.
+ * (not stored) or a DEVICE buffer of n_params floats.  Buffers must not overlap
+ * one another (ES_EINVAL).
  */
 int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
                        float* d_avg_grad, float lr, float mu);

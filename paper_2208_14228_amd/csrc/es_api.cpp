@@ -259,6 +259,14 @@ int check_ctx_call(es_handle* h, uint32_t est)
 
 int aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 
+// true if two buffers of `bytes` bytes each share an address (null = absent buffer)
+bool overlap(const void* a, const void* b, uint64_t bytes)
+{
+    if (!a || !b || bytes == 0) return false;
+    const uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+    return x < y + bytes && y < x + bytes;
+}
+
 // Makes the handle's device current for the duration of a call and puts the
 // caller's device back afterwards (the handle lives on the device that was
 // current at es_init).
@@ -673,8 +681,6 @@ int es_dropout_mask(es_handle* h, uint32_t est, uint32_t state_seg, uint8_t* d_m
 static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr, float mu)
 {
     if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
-    int rc = es_stage_fence(h);
-    if (rc != ES_OK) return rc;
     // gradients taken in place must not overlap what this launch writes
     for (uint32_t k = 0; k < h->in_place.n; ++k) {
         const uintptr_t g = (uintptr_t)h->in_place.ptr[k], sz = h->P * sizeof(float);
@@ -683,6 +689,8 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
             if (o && g < b + sz && b < g + sz) return ES_EINVAL;
         }
     }
+    int rc = es_stage_fence(h);
+    if (rc != ES_OK) return rc;
     // gradients taken in place: point their ranks at caller memory for this launch only
     ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
     const hipError_t launched = launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N,
@@ -713,6 +721,10 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_
     DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum || !d_avg_grad)) return ES_EINVAL;
     if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
+    const uint64_t vec_bytes = h->P * sizeof(float);
+    if (overlap(d_param, d_momentum, vec_bytes) || overlap(d_param, d_avg_grad, vec_bytes) ||
+        overlap(d_momentum, d_avg_grad, vec_bytes))
+        return ES_EINVAL;
     ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu));
     return ES_OK;
 }
@@ -733,6 +745,10 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum, float* d
     DeviceGuard guard__(h);
     if (h->P && (!d_param || !d_momentum)) return ES_EINVAL;
     if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
+    const uint64_t vec_bytes = h->P * sizeof(float);
+    if (overlap(d_param, d_momentum, vec_bytes) || overlap(d_param, d_avg_grad, vec_bytes) ||
+        overlap(d_momentum, d_avg_grad, vec_bytes))
+        return ES_EINVAL;
     return reduce_common(h, d_avg_grad, d_param, d_momentum, lr, mu);
 }
 

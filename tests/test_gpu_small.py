@@ -292,6 +292,15 @@ def test_state_errors_and_argument_checks():
         assert B.es_ctx_save(h, 0) == B.ES_ESTATE                             # bindings dropped
         assert B.es_ctx_switch(h, 0, 1) == B.ES_EINVAL                        # different workers now
         assert B.es_sync(h) == B.ES_OK
+        # parameters, momentum and averaged gradient must be three separate buffers
+        pp, vv, aa = job.p.data_ptr(), job.v.data_ptr(), job.avg.data_ptr()
+        assert B.es_sgd_step(h, pp, pp, aa, 0.1, 0.9) == B.ES_EINVAL
+        assert B.es_sgd_step(h, pp, vv, pp + 16, 0.1, 0.9) == B.ES_EINVAL
+        assert B.es_sgd_step(h, pp, vv, aa, 0.1, 0.9) == B.ES_OK
+        assert B.es_reduce_sgd_step(h, pp, pp + 64, 0, 0.1, 0.9) == B.ES_EINVAL
+        assert B.es_reduce_sgd_step(h, pp, vv, vv, 0.1, 0.9) == B.ES_EINVAL
+        assert B.es_reduce_sgd_step(h, pp, vv, 0, 0.1, 0.9) == B.ES_ESTATE     # valid buffers, nothing staged
+        assert B.es_sync(h) == B.ES_OK
         st, q = B.es_query(h)
         assert st == 0 and q["n_params"] == 1024 and q["n_buckets"] == 2 and q["ctx_bytes"] == 80 and q["n_workers"] == 2
     finally:
