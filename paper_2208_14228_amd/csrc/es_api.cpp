@@ -144,8 +144,21 @@ void plan_tiles(const std::vector<es_bucket>& buckets, uint32_t N, uint32_t A, u
             const uint64_t lo = std::min<uint64_t>(L, (uint64_t)c * CL);
             const uint64_t hi = std::min<uint64_t>(L, lo + CL);
             uint64_t a = lo;
+            // A chunk that starts off a 16-byte boundary opens with a tile that ends on one, so
+            // that only this tile has scalar leading elements: just the 1-3 odd elements when big
+            // tiles follow, else a tile a little short of T.
+            const uint64_t mis = (b.offset_elems + lo) & 3;
+            if (mis && lo < hi) {
+                const uint64_t odd = 4 - mis;
+                Tile t;
+                t.off = b.offset_elems + a;
+                t.len = (uint32_t)((TB && a + odd + TB <= hi) ? odd : std::min<uint64_t>(hi - a, T - mis));
+                t.rank0 = c;
+                small.push_back(t);
+                a += t.len;
+            }
             // full, 16-byte aligned big tiles first; the remainder of the chunk in small tiles
-            if (TB && ((b.offset_elems + lo) & 3) == 0) {
+            if (TB && ((b.offset_elems + a) & 3) == 0) {
                 for (; a + TB <= hi; a += TB) {
                     Tile t;
                     t.off = b.offset_elems + a;

@@ -63,3 +63,31 @@ def test_rejects_bad_arguments():
     assert B.es_plan_tiles(2, 8, [(0, 4)], 1, 2048, 0)[0] == B.ES_EINVAL     # layout does not cover
     assert B.es_plan_tiles(0, 8, [(0, 8)], 1, 2048, 0)[0] == B.ES_EINVAL
     assert B.es_plan_tiles(2, 8, [(0, 8)], 1, 2048, 0)[0] == B.ES_OK
+
+
+def test_only_the_first_tile_of_a_chunk_may_start_unaligned():
+    """Chunk boundaries off a 16-byte boundary (alignment 1 or 2, odd lengths): the chunk opens
+    with a tile that ends on a boundary, every later tile starts on one, and big tiles are
+    still used."""
+    for N, A in ((3, 1), (7, 1), (16, 1), (5, 2), (6, 3)):
+        lay = buckets.custom([N * 40000 + 5, 1001, 3, N * 300000 + 7, 2])
+        bstart = [o for o, _ in lay.buckets]
+        for tile, big in ((2048, 0), (2048, 32), (256, 8)):
+            n_big, _ = check(N, lay, A, tile, big)
+            st, _, tiles = B.es_plan_tiles(N, lay.n_params, lay.buckets, A, tile, big)
+            first_of_chunk = {}
+            for off, ln, r0 in tiles:
+                b = int(np.searchsorted(bstart, off, side="right")) - 1
+                first_of_chunk[(b, r0)] = min(first_of_chunk.get((b, r0), off), off)
+            unaligned_chunks = 0
+            for off, ln, r0 in tiles:
+                b = int(np.searchsorted(bstart, off, side="right")) - 1
+                if off != first_of_chunk[(b, r0)]:
+                    assert off % 4 == 0, (N, A, tile, big, off, ln, r0)
+                elif off % 4:
+                    unaligned_chunks += 1
+                    assert (off + ln) % 4 == 0 or ln < 4 or off + ln == lay.buckets[b][0] + oracle.chunk_bounds(
+                        lay.buckets[b][1], N, A, r0)[1]
+            assert unaligned_chunks > 0                       # the case is really exercised
+            if big:
+                assert n_big * 256 * big * 4 > 0.5 * lay.n_params
