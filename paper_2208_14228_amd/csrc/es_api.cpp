@@ -619,13 +619,13 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
                 if (rc != ES_OK) return rc;
                 ordered = true;
             }
-            if ((((uintptr_t)src | (uintptr_t)dst) & 15) != 0) {
-                ES_HIP(h, launch_copy_f32(h->s_stage, dst, src, len));      // unaligned: own launch
+            if ((((uintptr_t)src ^ (uintptr_t)dst) & 15) != 0) {
+                // source and destination off a 16-byte boundary by different amounts: own launch
+                ES_HIP(h, launch_copy_f32(h->s_stage, dst, src, len));
             } else {
                 // extend the previous run when source and destination both continue it
                 uint32_t& nr = runs.n_runs;
-                if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst &&
-                    (runs.n[nr - 1] & 3) == 0) {
+                if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst) {
                     runs.n[nr - 1] += len;
                 } else {
                     if (nr == (uint32_t)kMaxRuns) {

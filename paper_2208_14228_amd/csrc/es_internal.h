@@ -78,7 +78,7 @@ constexpr int kMaxRuns = 32;
 struct CopyRuns {
     float*       dst[kMaxRuns];
     const float* src[kMaxRuns];
-    uint64_t     n[kMaxRuns];               // floats; dst and src 16-byte aligned
+    uint64_t     n[kMaxRuns];               // floats; dst and src equally far off a 16-byte boundary
     uint32_t     first_block[kMaxRuns + 1]; // prefix sums of workgroups per run
     uint32_t     n_runs;
 };

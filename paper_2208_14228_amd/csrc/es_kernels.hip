@@ -604,32 +604,50 @@ hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part
 // ---------------------------------------------------------------------------
 // One 16-byte vector per lane and streaming hints on both sides measured fastest
 // on MI355X (about 6.5 TB/s read+write; four vectors per lane: 4.6 TB/s).
-__global__ __launch_bounds__(kCopyBlock) void k_copy_f4(float* __restrict__ dst,
-                                                    const float* __restrict__ src, uint64_t n)
+//
+// Source and destination need not be 16-byte aligned as long as they are off by the
+// same amount (the usual case: a bucket at the same odd offset in the flat gradient
+// and in the slot): the 1-3 elements up to the first boundary and the 0-3 after the
+// last whole vector are copied one by one by the first workgroup.
+__device__ __forceinline__ void copy_span(float* __restrict__ dst, const float* __restrict__ src,
+                                          uint64_t n, uint32_t block, uint32_t lane, uint32_t lanes)
 {
-    const uint64_t nvec = n >> 2;
-    const uint64_t i = (uint64_t)blockIdx.x * kCopyBlock + threadIdx.x;
+    uint64_t head = ((16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15) >> 2;
+    if (head > n) head = n;
+    const float* __restrict__ sb = src + head;
+    float* __restrict__ db = dst + head;
+    const uint64_t nb = n - head;
+    const uint64_t nvec = nb >> 2;
+    const uint64_t i = (uint64_t)block * lanes + lane;
     if (i < nvec) {
-        const f4 x = ld4<true>(src + 4 * i);
-        __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
+        const f4 x = ld4<true>(sb + 4 * i);
+        __builtin_nontemporal_store(x, reinterpret_cast<f4*>(db + 4 * i));
     }
-    if (blockIdx.x == 0) {
-        const uint64_t e = 4 * nvec + threadIdx.x;
-        if (e < n) dst[e] = src[e];
+    if (block == 0) {
+        if (lane < head) dst[lane] = src[lane];
+        const uint64_t e = 4 * nvec + lane;
+        if (lane < 4 && e < nb) db[e] = sb[e];
     }
 }
 
+__global__ __launch_bounds__(kCopyBlock) void k_copy_f4(float* __restrict__ dst,
+                                                    const float* __restrict__ src, uint64_t n)
+{
+    copy_span(dst, src, n, blockIdx.x, threadIdx.x, kCopyBlock);
+}
+
+// Source and destination off by different amounts: element by element, still streaming.
 __global__ __launch_bounds__(kBlock) void k_copy_f1(float* __restrict__ dst,
                                                     const float* __restrict__ src, uint64_t n)
 {
     const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i < n) dst[i] = src[i];
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n)
 {
     if (n == 0) return hipSuccess;
-    if ((((uintptr_t)dst | (uintptr_t)src) & 15) == 0) {
+    if ((((uintptr_t)dst ^ (uintptr_t)src) & 15) == 0) {
         uint64_t blocks = ((n >> 2) + kCopyBlock - 1) / kCopyBlock;
         if (blocks == 0) blocks = 1;
         hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kCopyBlock), 0, s, dst, src, n);
@@ -642,26 +660,14 @@ hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t
 
 // Batched staging: the runs arrive as a kernel argument (no table upload); a
 // workgroup finds its run by scanning the prefix sums (wave-uniform, scalar).
+// Every run has source and destination off a 16-byte boundary by the same amount.
 template <int BS>
 __global__ __launch_bounds__(BS) void k_copy_runs(const CopyRuns runs)
 {
     uint32_t r = 0;
     if (runs.n_runs > 1)
         while (r + 1 < runs.n_runs && blockIdx.x >= runs.first_block[r + 1]) ++r;
-    const uint64_t n = runs.n[r];
-    const uint64_t nvec = n >> 2;
-    const float* __restrict__ src = runs.src[r];
-    float* __restrict__ dst = runs.dst[r];
-    const uint32_t b = blockIdx.x - runs.first_block[r];
-    const uint64_t i = (uint64_t)b * BS + threadIdx.x;
-    if (i < nvec) {
-        const f4 x = ld4<true>(src + 4 * i);
-        __builtin_nontemporal_store(x, reinterpret_cast<f4*>(dst + 4 * i));
-    }
-    if (b == 0) {
-        const uint64_t e = 4 * nvec + threadIdx.x;
-        if (e < n) dst[e] = src[e];
-    }
+    copy_span(runs.dst[r], runs.src[r], runs.n[r], blockIdx.x - runs.first_block[r], threadIdx.x, BS);
 }
 
 hipError_t launch_copy_runs(hipStream_t s, const CopyRuns& runs)

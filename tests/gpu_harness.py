@@ -92,9 +92,12 @@ def init_contexts(sc: S.Scenario, job: ESTJob) -> None:
 
 def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=False,
               sync_each_est=False, masks: Optional[Dict] = None, mask_check=None,
-              steps: Optional[Sequence[int]] = None, batched=False, store_avg=True) -> None:
+              steps: Optional[Sequence[int]] = None, batched=False, store_avg=True,
+              src_shift=0) -> None:
     """``batched``: one flat gradient vector per EST handed over with es_accumulate_batch (what
-    bench.py times) instead of one tensor and one es_accumulate per bucket."""
+    bench.py times) instead of one tensor and one es_accumulate per bucket; ``src_shift`` moves
+    that vector 0-3 elements off its 16-byte boundary (sources then sit differently from the
+    slots, or equally for buckets at a matching odd offset)."""
     mask = torch.empty(sc.mask_n, dtype=torch.uint8, device=DEV) if sc.mask_n else None
     sched = g.schedule()
     for t in (range(sc.steps) if steps is None else steps):
@@ -117,7 +120,8 @@ def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=
                 bn_add_live(sc, job, e, S.bn_delta(sc, t, e, DEV))
             with job.stream_ctx():
                 if batched:
-                    flat = torch.empty(sc.layout.n_params, dtype=torch.float32, device=DEV)
+                    flat = torch.empty(sc.layout.n_params + 4, dtype=torch.float32,
+                                       device=DEV)[src_shift:src_shift + sc.layout.n_params]
                     for b, (off, ln) in enumerate(sc.layout.buckets):
                         synth.gradient(sc.layout, b, sc.seed, t, e, DEV, out=flat[off:off + ln])
                     keep.append(flat)
@@ -162,7 +166,7 @@ def collect(sc: S.Scenario, job: ESTJob, masks: Dict) -> S.Result:
 
 
 def run_gpu(sc: S.Scenario, g: Grouping, fused=False, use_switch=False, use_streams=True,
-            options=None, live_alloc=None) -> S.Result:
+            options=None, live_alloc=None, batched=False, src_shift=0) -> S.Result:
     print(f"[gpu-run] N={sc.n_logical} P={sc.layout.n_params} A={sc.chunk_align} seed={sc.seed:#x} "
           f"grouping={g.name} fused={fused} switch={use_switch} streams={use_streams} opts={options}",
           flush=True)
@@ -170,7 +174,7 @@ def run_gpu(sc: S.Scenario, g: Grouping, fused=False, use_switch=False, use_stre
     try:
         init_contexts(sc, job)
         masks: Dict = {}
-        run_steps(sc, job, g, fused, use_switch, masks=masks)
+        run_steps(sc, job, g, fused, use_switch, masks=masks, batched=batched, src_shift=src_shift)
         return collect(sc, job, masks)
     finally:
         job.close()

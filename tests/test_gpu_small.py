@@ -618,10 +618,43 @@ def test_random_layouts_groupings_and_launch_shapes():
                    "reduce_big_unroll": int(rng.choice([0, 0, 8, 16, 32]))}
         fused, switch = bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
         streams = [True, "two", "one", False][int(rng.integers(0, 4))]
-        what = f"case {case}: N={N} A={A} lens={lens} grouping={g.name} {options} fused={fused} streams={streams}"
+        batched, shift = bool(rng.integers(0, 2)), int(rng.integers(0, 4))
+        what = (f"case {case}: N={N} A={A} lens={lens} grouping={g.name} {options} fused={fused} "
+                f"streams={streams} batched={batched} src_shift={shift}")
         print("[gpu-case]", what, flush=True)
         sc = S.Scenario(N, buckets.custom(lens, fan_in=5), A, 9000 + case, steps=2,
                         mask_n=int(rng.integers(0, 300)), bn_channels=(3, int(rng.integers(1, 70))))
         ref = S.run_ddp_reference(sc)
-        S.assert_same(G.run_gpu(sc, g, fused=fused, use_switch=switch, use_streams=streams, options=options),
-                      ref, what)
+        S.assert_same(G.run_gpu(sc, g, fused=fused, use_switch=switch, use_streams=streams, options=options,
+                                batched=batched, src_shift=shift), ref, what)
+
+
+def test_staging_from_sources_off_a_16_byte_boundary():
+    """Buckets at odd offsets, flat sources shifted by 0-3 elements: the vector copy with
+    leading and trailing single elements (source and slot equally far off a boundary) and the
+    element-wise copy (off by different amounts), batched and per bucket, give the same bits."""
+    N = 3
+    lay = buckets.custom([4097, 3, 8190, 1, 2, 70001, 5], fan_in=2)      # offsets 1, 0, 2, 3, 1, 2 (mod 4)
+    sc = S.Scenario(N, lay, 1, 404, steps=1)
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([N])
+    for shift in range(4):
+        S.assert_same(G.run_gpu(sc, g, fused=True, batched=True, src_shift=shift, use_streams="one"),
+                      ref, f"batched shift {shift}")
+    # per bucket through es_accumulate, sources cut out of one shifted flat vector
+    job = G.make_job(sc, g, use_streams="one")
+    try:
+        for shift in range(4):
+            keep = []
+            for e in range(N):
+                flat = torch.empty(lay.n_params + 4, device=G.DEV)[shift:shift + lay.n_params]
+                for b, (off, ln) in enumerate(lay.buckets):
+                    with job.stream_ctx():
+                        synth.gradient(lay, b, sc.seed, 0, e, G.DEV, out=flat[off:off + ln])
+                    job.accumulate(e, b, flat[off:off + ln])
+                keep.append(flat)
+            job.ring_order_reduce()
+            job.sync(); torch.cuda.synchronize()
+            assert np.array_equal(bits(job.avg.cpu().numpy()), bits(ref.avg)), f"per bucket shift {shift}"
+    finally:
+        job.close()
