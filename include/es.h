@@ -314,13 +314,15 @@ int es_sync(es_handle* h);
  *   "reduce_tile_elems"   elements of one bucket chunk handled by one workgroup
  *                         (multiple of 4, 256 .. 65536)
  *   "reduce_unroll"       16-byte vectors per lane in flight per rank (1, 2, 4)
- *   "reduce_rank_batch"   ranks loaded before their adds are issued (1, 2, 4, 8, 16)
+ *   "reduce_rank_batch"   ranks loaded before their adds are issued (1, 2, 4, 8, 16;
+ *                         default 8, or the largest power of two <= n_logical below that)
  *   "nontemporal"         0/1: streaming hint on gradient loads
  *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the fused
  *                         update (default: 1 if both vectors exceed 224 MiB, else 0)
  *   "reduce_big_unroll"   0, 8, 16 or 32: if not 0, full aligned stretches of a ring chunk
  *                         are handled in big tiles of 256 * value * 4 elements (long
- *                         contiguous reads per gradient stream; pays off for large N)
+ *                         contiguous reads per gradient stream; default 32 from
+ *                         n_logical = 11 on, else 0)
  *   "reduce_big_rank_batch"  ranks loaded ahead in big tiles (1, 2, 4; unroll * batch <= 32)
  * Returns ES_EINVAL for unknown names or values.
  */

@@ -330,8 +330,11 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
         h->slot_of.resize(h->N);
         for (uint32_t e = 0; e < h->N; ++e) h->slot_of[e] = e;
         h->accumulated.assign((size_t)h->N * h->buckets.size(), 0);
+        // fewer ranks than the default batch: the largest power of two that fits, so that the
+        // opening loads of a fold are still issued together (measured +4 % at N = 5..7)
+        while (h->shape.rank_batch > 1 && (uint32_t)h->shape.rank_batch > h->N) h->shape.rank_batch /= 2;
         // many concurrent gradient streams: long contiguous reads per stream pay off (measured)
-        if (h->N >= 16) { h->shape.big_unroll = 32; h->shape.big_rank_batch = 1; }
+        if (h->N >= 11) { h->shape.big_unroll = 32; h->shape.big_rank_batch = 1; }
         // parameters + momentum that fit in the Infinity Cache stay cacheable between steps
         h->shape.nontemporal_pv = (2 * h->P * sizeof(float) > (224ull << 20)) ? 1 : 0;
         h->workers.resize(1);

@@ -46,7 +46,7 @@ def test_ragged_layouts(N, A):
 def test_benchmark_layouts():
     for cid in (1, 2, 3, 4, 5):
         cfg = configs.config(cid)
-        big = 32 if cfg.n_logical >= 16 else 0
+        big = 32 if cfg.n_logical >= 11 else 0
         n_big, n = check(cfg.n_logical, cfg.layout, cfg.chunk_align, 2048, big)
         if big:                                               # most of the work is in big tiles
             assert n_big * 32768 > 0.9 * cfg.layout.n_params
