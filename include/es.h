@@ -318,7 +318,7 @@ int es_sync(es_handle* h);
  *                         default 8, or the largest power of two <= n_logical below that)
  *   "nontemporal"         0/1: streaming hint on gradient loads
  *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the fused
- *                         update (default: 1 if both vectors exceed 224 MiB, else 0)
+ *                         update (default: 1 if both vectors together exceed 284 MiB, else 0)
  *   "reduce_big_unroll"   0, 8, 16 or 32: if not 0, full aligned stretches of a ring chunk
  *                         are handled in big tiles of 256 * value * 4 elements (long
  *                         contiguous reads per gradient stream; default 32 from

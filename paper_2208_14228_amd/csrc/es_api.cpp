@@ -335,8 +335,9 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
         while (h->shape.rank_batch > 1 && (uint32_t)h->shape.rank_batch > h->N) h->shape.rank_batch /= 2;
         // many concurrent gradient streams: long contiguous reads per stream pay off (measured)
         if (h->N >= 11) { h->shape.big_unroll = 32; h->shape.big_rank_batch = 1; }
-        // parameters + momentum that fit in the Infinity Cache stay cacheable between steps
-        h->shape.nontemporal_pv = (2 * h->P * sizeof(float) > (224ull << 20)) ? 1 : 0;
+        // parameters + momentum that fit in the Infinity Cache and the L2s stay cacheable between
+        // steps (measured crossover at N = 8: between 282 and 290 MiB)
+        h->shape.nontemporal_pv = (2 * h->P * sizeof(float) > (284ull << 20)) ? 1 : 0;
         h->workers.resize(1);
         h->workers[0].live.assign(h->seg_bytes.size(), nullptr);
     } catch (const std::bad_alloc&) {
