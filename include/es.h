@@ -106,7 +106,9 @@ int es_destroy(es_handle* h);
  * afterwards; a save or an accumulate starts after the work already enqueued
  * on main; the reduce starts after every accumulate of the step.  If all three
  * are the same stream no events are used.  Must not be called while work of
- * this handle is in flight (call es_sync first).
+ * this handle is in flight (call es_sync first).  The streams stay the
+ * caller's; they must exist until es_destroy (which waits on them) or until
+ * another es_set_streams replaces them.
  */
 int es_set_streams(es_handle* h, void* main, void* ctx, void* stage);
 
