@@ -338,9 +338,10 @@ int es_get_option(es_handle* h, const char* name, int64_t* value);
  * rank whose gradient opens the fold for every element of the tile (= the chunk
  * index, see es_ring_order_reduce).  The first *n_big tiles are big tiles of
  * 256 * big_unroll * 4 elements (full, offset a multiple of 4); all others have
- * at most tile_elems elements.  A chunk that starts off a 16-byte boundary opens
- * with a shorter tile that ends on one, so every later tile of the chunk starts
- * aligned.  Tiles are disjoint and cover [0, n_params).
+ * at most tile_elems elements.  A chunk that starts inside a 128-byte line (32
+ * elements; 16 bytes if tile_elems is not a multiple of 32) opens with a shorter
+ * tile that ends on a line boundary, so every later tile of the chunk starts on
+ * one.  Tiles are disjoint and cover [0, n_params).
  *   out       HOST array of `capacity` entries, or NULL to query the counts only
  * Returns ES_EINVAL for an invalid layout or option value, or capacity too small.
  */

@@ -144,12 +144,15 @@ void plan_tiles(const std::vector<es_bucket>& buckets, uint32_t N, uint32_t A, u
             const uint64_t lo = std::min<uint64_t>(L, (uint64_t)c * CL);
             const uint64_t hi = std::min<uint64_t>(L, lo + CL);
             uint64_t a = lo;
-            // A chunk that starts off a 16-byte boundary opens with a tile that ends on one, so
-            // that only this tile has scalar leading elements: just the 1-3 odd elements when big
-            // tiles follow, else a tile a little short of T.
-            const uint64_t mis = (b.offset_elems + lo) & 3;
+            // A chunk that starts inside a 128-byte line opens with a tile that ends on a line
+            // boundary: every later tile then starts on one (a line shared by two workgroups
+            // is fetched twice, by two compute dies), only the opening tile can have scalar
+            // leading elements, and big tiles stay usable.  The opening tile is just the
+            // elements up to the boundary when big tiles follow, else a tile a little short of T.
+            const uint64_t line = (T % 32 == 0) ? 32 : 4;                 // elements
+            const uint64_t mis = (b.offset_elems + lo) & (line - 1);
             if (mis && lo < hi) {
-                const uint64_t odd = 4 - mis;
+                const uint64_t odd = line - mis;
                 Tile t;
                 t.off = b.offset_elems + a;
                 t.len = (uint32_t)((TB && a + odd + TB <= hi) ? odd : std::min<uint64_t>(hi - a, T - mis));
@@ -607,6 +610,7 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
     runs.first_block[0] = 0;
     auto flush = [&]() -> int {
         if (runs.n_runs == 0) return ES_OK;
+        for (uint32_t k = runs.n_runs + 1; k <= (uint32_t)kMaxRuns; ++k) runs.first_block[k] = 0xFFFFFFFFu;
         ES_HIP(h, launch_copy_runs(h->s_stage, runs));
         runs.n_runs = 0;
         runs.first_block[0] = 0;
@@ -623,30 +627,25 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
                 if (rc != ES_OK) return rc;
                 ordered = true;
             }
-            if ((((uintptr_t)src ^ (uintptr_t)dst) & 15) != 0) {
-                // source and destination off a 16-byte boundary by different amounts: own launch
-                ES_HIP(h, launch_copy_f32(h->s_stage, dst, src, len));
+            // extend the previous run when source and destination both continue it
+            uint32_t& nr = runs.n_runs;
+            if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst) {
+                runs.n[nr - 1] += len;
             } else {
-                // extend the previous run when source and destination both continue it
-                uint32_t& nr = runs.n_runs;
-                if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst) {
-                    runs.n[nr - 1] += len;
-                } else {
-                    if (nr == (uint32_t)kMaxRuns) {
-                        int rc = flush();
-                        if (rc != ES_OK) return rc;
-                    }
-                    runs.dst[nr] = dst;
-                    runs.src[nr] = src;
-                    runs.n[nr] = len;
-                    ++nr;
+                if (nr == (uint32_t)kMaxRuns) {
+                    int rc = flush();
+                    if (rc != ES_OK) return rc;
                 }
-                const uint64_t vec = runs.n[nr - 1] >> 2;
-                uint64_t blocks = (vec + kCopyBlock - 1) / kCopyBlock;
-                if (blocks == 0) blocks = 1;
-                if (runs.first_block[nr - 1] + blocks > 0x7fffffffull) return ES_EINVAL;
-                runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;
+                runs.dst[nr] = dst;
+                runs.src[nr] = src;
+                runs.n[nr] = len;
+                ++nr;
             }
+            const uint64_t vec = runs.n[nr - 1] >> 2;
+            uint64_t blocks = (vec + kCopyBlock - 1) / kCopyBlock;
+            if (blocks == 0) blocks = 1;
+            if (runs.first_block[nr - 1] + blocks > 0x7fffffffull) return ES_EINVAL;
+            runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;
             h->stage_pending = true;
         }
         h->accumulated[(size_t)est * nb + b] = 1;

@@ -74,12 +74,13 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
 hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n);
 
 // Several contiguous runs copied by one launch (batched gradient staging).
-constexpr int kMaxRuns = 32;
+constexpr int kMaxRuns = 16;                // the prefix sums then travel in one 64-byte scalar load
 struct CopyRuns {
     float*       dst[kMaxRuns];
     const float* src[kMaxRuns];
-    uint64_t     n[kMaxRuns];               // floats; dst and src equally far off a 16-byte boundary
-    uint32_t     first_block[kMaxRuns + 1]; // prefix sums of workgroups per run
+    uint64_t     n[kMaxRuns];               // floats; dst and src 4-byte aligned
+    uint32_t     first_block[kMaxRuns + 1]; // prefix sums of workgroups per run; [n_runs] = total,
+                                            // entries after it 0xFFFFFFFF
     uint32_t     n_runs;
 };
 hipError_t launch_copy_runs(hipStream_t s, const CopyRuns& runs);

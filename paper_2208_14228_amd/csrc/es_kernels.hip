@@ -605,14 +605,22 @@ hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part
 // One 16-byte vector per lane and streaming hints on both sides measured fastest
 // on MI355X (about 6.5 TB/s read+write; four vectors per lane: 4.6 TB/s).
 //
-// Source and destination need not be 16-byte aligned as long as they are off by the
-// same amount (the usual case: a bucket at the same odd offset in the flat gradient
-// and in the slot): the 1-3 elements up to the first boundary and the 0-3 after the
-// last whole vector are copied one by one by the first workgroup.
+// Neither side needs 16-byte alignment.  Each wave moves 1 KiB that starts on a 128-byte
+// line of the destination (a piece that starts inside a line shares that line with the
+// neighbouring workgroup on another compute die, and the line travels twice: measured
+// -13 % for buckets at offsets that are not multiples of 128 bytes).  The elements up to
+// the first such line and the 0-3 after the last whole vector are copied one by one by the
+// first workgroup.  Loads are 16 bytes wide at whatever 4-byte-aligned address that gives
+// on the source side (global memory needs dword alignment only): when source and
+// destination are equally far off a line - the usual case, a bucket at the same offset in
+// a flat gradient and in the slot - they are aligned alike.
+typedef float f4_dword_aligned __attribute__((ext_vector_type(4), aligned(4)));
+
 __device__ __forceinline__ void copy_span(float* __restrict__ dst, const float* __restrict__ src,
                                           uint64_t n, uint32_t block, uint32_t lane, uint32_t lanes)
 {
-    uint64_t head = ((16 - (reinterpret_cast<uintptr_t>(dst) & 15)) & 15) >> 2;
+    constexpr uintptr_t kAlign = 128;                    // 1 KiB alignment measured no better
+    uint64_t head = ((kAlign - (reinterpret_cast<uintptr_t>(dst) & (kAlign - 1))) & (kAlign - 1)) >> 2;
     if (head > n) head = n;
     const float* __restrict__ sb = src + head;
     float* __restrict__ db = dst + head;
@@ -620,11 +628,11 @@ __device__ __forceinline__ void copy_span(float* __restrict__ dst, const float* 
     const uint64_t nvec = nb >> 2;
     const uint64_t i = (uint64_t)block * lanes + lane;
     if (i < nvec) {
-        const f4 x = ld4<true>(sb + 4 * i);
+        const f4 x = __builtin_nontemporal_load(reinterpret_cast<const f4_dword_aligned*>(sb + 4 * i));
         __builtin_nontemporal_store(x, reinterpret_cast<f4*>(db + 4 * i));
     }
     if (block == 0) {
-        if (lane < head) dst[lane] = src[lane];
+        for (uint64_t e = lane; e < head; e += lanes) dst[e] = src[e];
         const uint64_t e = 4 * nvec + lane;
         if (lane < 4 && e < nb) db[e] = sb[e];
     }
@@ -636,37 +644,30 @@ __global__ __launch_bounds__(kCopyBlock) void k_copy_f4(float* __restrict__ dst,
     copy_span(dst, src, n, blockIdx.x, threadIdx.x, kCopyBlock);
 }
 
-// Source and destination off by different amounts: element by element, still streaming.
-__global__ __launch_bounds__(kBlock) void k_copy_f1(float* __restrict__ dst,
-                                                    const float* __restrict__ src, uint64_t n)
-{
-    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
-}
-
 hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n)
 {
     if (n == 0) return hipSuccess;
-    if ((((uintptr_t)dst ^ (uintptr_t)src) & 15) == 0) {
-        uint64_t blocks = ((n >> 2) + kCopyBlock - 1) / kCopyBlock;
-        if (blocks == 0) blocks = 1;
-        hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kCopyBlock), 0, s, dst, src, n);
-    } else {
-        const uint64_t blocks = (n + kBlock - 1) / kBlock;
-        hipLaunchKernelGGL(k_copy_f1, dim3((uint32_t)blocks), dim3(kBlock), 0, s, dst, src, n);
-    }
+    uint64_t blocks = ((n >> 2) + kCopyBlock - 1) / kCopyBlock;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(k_copy_f4, dim3((uint32_t)blocks), dim3(kCopyBlock), 0, s, dst, src, n);
     return hipGetLastError();
 }
 
 // Batched staging: the runs arrive as a kernel argument (no table upload); a
-// workgroup finds its run by scanning the prefix sums (wave-uniform, scalar).
-// Every run has source and destination off a 16-byte boundary by the same amount.
+// workgroup finds its run from the prefix sums (wave-uniform, scalar).
 template <int BS>
 __global__ __launch_bounds__(BS) void k_copy_runs(const CopyRuns runs)
 {
+    // the run of this workgroup = how many later runs start at or before it.  All prefix sums
+    // are fetched at once (independent scalar loads of the kernel argument) and compared in
+    // registers: a dependent load per run would be most of this short workgroup's life.
+    // (Entries past the last run hold 0xFFFFFFFF, so the count needs no bound.)  A single run -
+    // one flat gradient vector, the common case - skips the lookup: it costs 2.7 % there.
     uint32_t r = 0;
-    if (runs.n_runs > 1)
-        while (r + 1 < runs.n_runs && blockIdx.x >= runs.first_block[r + 1]) ++r;
+    if (runs.n_runs > 1) {
+#pragma unroll
+        for (int k = 1; k < kMaxRuns; ++k) r += blockIdx.x >= runs.first_block[k] ? 1u : 0u;
+    }
     copy_span(runs.dst[r], runs.src[r], runs.n[r], blockIdx.x - runs.first_block[r], threadIdx.x, BS);
 }
 

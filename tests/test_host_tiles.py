@@ -66,8 +66,8 @@ def test_rejects_bad_arguments():
 
 
 def test_only_the_first_tile_of_a_chunk_may_start_unaligned():
-    """Chunk boundaries off a 16-byte boundary (alignment 1 or 2, odd lengths): the chunk opens
-    with a tile that ends on a boundary, every later tile starts on one, and big tiles are
+    """Chunk boundaries inside a 128-byte line (alignment 1 or 2, odd lengths): the chunk opens
+    with a tile that ends on a line boundary, every later tile starts on one, and big tiles are
     still used."""
     for N, A in ((3, 1), (7, 1), (16, 1), (5, 2), (6, 3)):
         lay = buckets.custom([N * 40000 + 5, 1001, 3, N * 300000 + 7, 2])
@@ -83,7 +83,7 @@ def test_only_the_first_tile_of_a_chunk_may_start_unaligned():
             for off, ln, r0 in tiles:
                 b = int(np.searchsorted(bstart, off, side="right")) - 1
                 if off != first_of_chunk[(b, r0)]:
-                    assert off % 4 == 0, (N, A, tile, big, off, ln, r0)
+                    assert off % 32 == 0, (N, A, tile, big, off, ln, r0)      # on a 128-byte line
                 elif off % 4:
                     unaligned_chunks += 1
                     assert (off + ln) % 4 == 0 or ln < 4 or off + ln == lay.buckets[b][0] + oracle.chunk_bounds(
