@@ -160,7 +160,9 @@ int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in);
  * gradient copy, §3.2 / §5.1.3; here device-to-device because all N gradient
  * sets fit in HBM).
  *   d_grad_bucket  DEVICE, len_elems floats of that bucket, 4-byte aligned
- *                  (16-byte aligned sources take the vector path).  If it
+ *                  (any such source is copied with 16-byte accesses; fastest
+ *                  when source and slot are equally far off a 128-byte line,
+ *                  as a bucket of one flat gradient vector is).  If it
  *                  equals es_grad_slot(est, bucket) nothing is copied and the
  *                  bucket is only marked as present (zero-copy production).
  * Exactly one call per (est, bucket) per global step: a second one returns
@@ -173,10 +175,10 @@ int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_gr
  * es_accumulate for several buckets of one EST at once (same rules per bucket).
  *   buckets         HOST array of n distinct bucket indices
  *   d_grad_buckets  HOST array of n DEVICE pointers, one source per bucket
- * All 16-byte-aligned sources are copied by a single kernel launch; sources that
- * continue each other in memory for buckets that are adjacent in the parameter
- * space are merged into one contiguous run.  Validation covers the whole batch
- * before anything is enqueued or marked.
+ * Up to 16 runs are copied by one kernel launch; sources that continue each other
+ * in memory for buckets that are adjacent in the parameter space are merged into
+ * one contiguous run (a flat gradient vector is one run).  Validation covers the
+ * whole batch before anything is enqueued or marked.
  */
 int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
                         const float* const* d_grad_buckets);
