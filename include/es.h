@@ -268,6 +268,25 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
 int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2);
 
 /*
+ * es_grad_sq_norm for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Needs no
+ * handle and calls no hipMalloc / hipFree or any allocating routine: the block
+ * partials go to a fixed 1 MiB array that is part of the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends).
+ * Same tree, same bits as es_grad_sq_norm on a vector of n elements.
+ *   d_vec    DEVICE, n floats, 16-byte aligned (may be NULL if n = 0)
+ *   n        <= 2^30 elements (262,144 block partials); larger n: ES_EINVAL
+ *   d_out2   DEVICE, 2 floats: [0] sum of squares, [1] its square root
+ *   stream   HOST value of a hipStream_t on the current device (NULL = null stream)
+ * Runs on the current HIP device.  All calls on one GPU share that GPU's array:
+ * calls that can overlap on one GPU (different streams without ordering between
+ * them) race and must be ordered by the caller; calls on one stream are safe.
+ * Nothing in the array has to start at zero (each call writes every partial it
+ * later reads), so nothing is cleared.  ES_EHIP if a HIP call fails.
+ */
+int es_grad_sq_norm_static(const float* d_vec, uint64_t n, float* d_out2, void* stream);
+
+/*
  * On-demand checkpoint (paper §3.2 "Adapting to elasticity"; §3.3 D1: the bucket
  * mapping travels with the checkpoint and is reinstated, never rebuilt).  Taken
  * between global steps when resources change; the job continues from it with the

@@ -81,6 +81,7 @@ _SIGS = {
     "es_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
     "es_reduce_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
     "es_grad_sq_norm": (ctypes.c_int, [_VP, _VP, _VP]),
+    "es_grad_sq_norm_static": (ctypes.c_int, [_VP, ctypes.c_uint64, _VP, _VP]),
     "es_checkpoint_bytes": (ctypes.c_uint64, [_VP]),
     "es_checkpoint_export": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP, ctypes.c_uint64]),
     "es_checkpoint_import": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP,
@@ -201,6 +202,7 @@ def es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
 
 
 def es_grad_sq_norm(h, d_vec, d_out2): return lib().es_grad_sq_norm(h, d_vec, d_out2)
+def es_grad_sq_norm_static(d_vec, n, d_out2, stream=0): return lib().es_grad_sq_norm_static(d_vec, n, d_out2, stream)
 def es_checkpoint_bytes(h): return lib().es_checkpoint_bytes(h)
 
 

@@ -754,6 +754,14 @@ int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2)
     return ES_OK;
 }
 
+int es_grad_sq_norm_static(const float* d_vec, uint64_t n, float* d_out2, void* stream)
+{
+    if (!d_out2 || (((uintptr_t)d_out2) & 3)) return ES_EINVAL;
+    if (n && (!d_vec || !aligned16(d_vec))) return ES_EINVAL;
+    if ((n + 4095) / 4096 > kStaticPartials) return ES_EINVAL;
+    return launch_sq_norm_static((hipStream_t)stream, d_vec, n, d_out2) == hipSuccess ? ES_OK : ES_EHIP;
+}
+
 int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum, float* d_avg_grad,
                        float lr, float mu)
 {

@@ -98,6 +98,12 @@ hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, ui
 // part: scratch of ceil(n / 4096) floats
 hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part, float* out);
 
+// The same with the block partials in a file-scope device array of kStaticPartials floats
+// (1 MiB per GPU): no allocation; n <= kStaticPartials * 4096, else hipErrorInvalidValue.
+// Runs on the current device.
+constexpr uint64_t kStaticPartials = 1ull << 18;
+hipError_t launch_sq_norm_static(hipStream_t s, const float* x, uint64_t n, float* out);
+
 hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, uint64_t n,
                                uint64_t threshold);
 

@@ -10,6 +10,8 @@
 //  - loads may be issued early and in any order, only the add chain is ordered.
 #include "es_internal.h"
 
+#include <mutex>
+
 namespace es {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
@@ -597,6 +599,48 @@ hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part
     if (nblk) hipLaunchKernelGGL(k_sq_partials, dim3((uint32_t)((nblk + 3) / 4)), dim3(kBlock), 0, s, x, n, nblk, part);
     hipLaunchKernelGGL(k_sq_final, dim3(1), dim3(kBlock), 0, s, part, nblk, out);
     return hipGetLastError();
+}
+
+// Block partials of the allocation-free norm: one array per GPU, part of the code
+// object, held until the process ends.  `scratch` is a host-side stand-in for the
+// symbol, not a device address: host code only ever uses the address that
+// hipGetSymbolAddress returned for the device in question.
+static __device__ __align__(256) float scratch[kStaticPartials];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+float* g_scratch_ptr[kMaxDevices] = {};          // per device: where that GPU's copy of `scratch` lives
+}
+
+// Device address of the current device's `scratch` (looked up once per device).
+static hipError_t static_partials(float** out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        float* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_sq_norm_static(hipStream_t s, const float* x, uint64_t n, float* out)
+{
+    if ((n + 4095) / 4096 > kStaticPartials) return hipErrorInvalidValue;
+    float* part = nullptr;
+    const hipError_t e = static_partials(&part);
+    if (e != hipSuccess) return e;
+    // k_sq_partials writes partials [0, nblk) before k_sq_final reads exactly those, so what
+    // an earlier call left in the array is never read and nothing has to be cleared
+    return launch_sq_norm(s, x, n, part, out);
 }
 
 // ---------------------------------------------------------------------------

@@ -74,6 +74,13 @@ def test_null_handle_is_rejected_everywhere():
     assert B.es_last_hip_error(0) == 0
 
 
+def test_allocation_free_norm_rejects_bad_arguments_before_any_device_work():
+    assert B.es_grad_sq_norm_static(16, 4, 0, 0) == B.ES_EINVAL                 # no output
+    assert B.es_grad_sq_norm_static(0, 4, 16, 0) == B.ES_EINVAL                 # no input
+    assert B.es_grad_sq_norm_static(20, 4, 16, 0) == B.ES_EINVAL                # input not 16-byte aligned
+    assert B.es_grad_sq_norm_static(16, (1 << 30) + 1, 16, 0) == B.ES_EINVAL    # beyond the fixed array
+
+
 def test_product_does_not_import_the_oracle():
     """The HIP path and its binding never touch oracle/ (and the oracle never imports them)."""
     pkg = os.path.join(ROOT, "paper_2208_14228_amd")
