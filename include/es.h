@@ -73,6 +73,9 @@ typedef struct es_bucket {
  *                    and the running mean / variance of every BatchNorm layer.
  *                    Copied by es_init.
  */
+typedef void* (*es_dev_alloc_fn)(size_t bytes, void* user);
+typedef void  (*es_dev_free_fn)(void* dev_ptr, void* user);
+
 typedef struct es_bucket_layout {
     uint64_t         n_params;
     uint32_t         n_buckets;
@@ -80,6 +83,22 @@ typedef struct es_bucket_layout {
     uint32_t         chunk_align;
     uint32_t         n_state_segs;
     const uint64_t*  state_seg_bytes;
+    /*
+     * Optional device allocator of the caller (e.g. a framework's caching allocator), so
+     * that the context arenas - N * n_params floats of gradient slots, the bulk of the
+     * job's memory - come out of the caller's pool.  Both NULL: hipMalloc / hipFree.
+     *   dev_alloc  returns a DEVICE pointer to `bytes` bytes on the device that is current
+     *              at the call, aligned to 256 bytes, or NULL if it cannot (-> ES_ENOMEM);
+     *              it must not throw or unwind through the library
+     *   dev_free   releases a pointer dev_alloc returned; called from es_set_grouping and
+     *              es_destroy after the handle's streams have been synchronised
+     *   user       passed back unchanged
+     * The functions must stay callable until es_destroy has returned.  Host-resident
+     * slots (option "host_slots") are pinned host memory and never go through them.
+     */
+    es_dev_alloc_fn  dev_alloc;
+    es_dev_free_fn   dev_free;
+    void*            user;
 } es_bucket_layout;
 
 /*
@@ -193,9 +212,9 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
  *                main; must stay unmodified until the reduce of this step has run and
  *                must not overlap that reduce's outputs (ES_EINVAL at the reduce).
  * Counts as the accumulate of every bucket of `est` (ES_ESTATE if one of them is
- * already present).  At most 8 ESTs per global step (ES_ESTATE beyond that; stage
- * the others with es_accumulate).  Nothing is enqueued; the effect ends with the
- * next reduce.
+ * already present).  Any number of ESTs may be taken this way (with all of them
+ * in place nothing is staged at all).  Nothing is enqueued; the effect ends with the
+ * next reduce that succeeds (a reduce that fails leaves the step as it was).
  */
 int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad);
 

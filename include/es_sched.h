@@ -96,7 +96,12 @@ int es_sched_best_mapping(uint32_t n_types, const double* capability, const uint
  * nEST, then lexicographically smaller N, then A.  The first min(top_k, number
  * of plans) are written to out; *n_out receives how many.
  *   available  n_types entries; the product of (available[i] + 1) must not
- *              exceed 2^20
+ *              exceed 2^20, and that product times max_p must not exceed 2^27
+ *              (ES_EINVAL otherwise).  Cost: one best-mapping search per count
+ *              vector, each on the order of n_types * max_p steps; measured on one
+ *              host core 0.4 s for 70,784 vectors at max_p = 1024, so the bound
+ *              keeps a call to a few seconds.  A scheduler that needs a larger space
+ *              enumerates it in slices (fix the count of one type per call).
  *   top_k      >= 1; out must hold top_k entries
  */
 int es_sched_enumerate(uint32_t n_types, const double* capability, const uint32_t* available,

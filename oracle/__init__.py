@@ -37,22 +37,36 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "es_oracle.c")
 _LIB = os.path.join(_HERE, "libes_oracle.so")
-CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-Wall"]
+_LIB_OMP = os.path.join(_HERE, "libes_oracle_omp.so")
+CFLAGS = ["-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared", "-Wall",
+          "-Wno-unknown-pragmas"]
 
 _lib = None
+_threaded = False
 
 
 def build(force: bool = False) -> str:
-    """Compile the C oracle with gcc.  Returns the path of the shared object."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", _LIB])
+    """Compile the C oracle with gcc: the single-threaded oracle, and the same file with -fopenmp
+    (used only for the all-core timing in bench.py).  Returns the path of the former."""
+    for out, extra in ((_LIB, []), (_LIB_OMP, ["-fopenmp"])):
+        if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+            subprocess.check_call(["gcc", *CFLAGS, *extra, _SRC, "-o", out])
     return _LIB
+
+
+def use_all_cores(on: bool) -> None:
+    """Switch every function of this module to the -fopenmp build of es_oracle.c (or back).
+    Same operations on the same operands; only bench.py's all-core timing asks for it."""
+    global _lib, _threaded
+    if on != _threaded:
+        _lib, _threaded = None, on
 
 
 def lib() -> ctypes.CDLL:
     global _lib
     if _lib is None:
-        L = ctypes.CDLL(build())
+        build()
+        L = ctypes.CDLL(_LIB_OMP if _threaded else _LIB)
         f32p = ctypes.POINTER(ctypes.c_float)
         u64p = ctypes.POINTER(ctypes.c_uint64)
         u32p = ctypes.POINTER(ctypes.c_uint32)

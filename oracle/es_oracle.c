@@ -22,6 +22,13 @@
  * The ring is simulated as message passing: N rank-private buffers, explicit
  * per-step messages that are snapshotted before any receiver applies them.
  * Nothing here is blocked, fused or reordered.
+ *
+ * The "omp parallel for" pragmas are ignored by the default build (no -fopenmp),
+ * which is the oracle the tests pin.  A second build of this same file with
+ * -fopenmp exists only so that bench.py can also time it on all host cores: in
+ * each ring step the N ranks post, and then consume, independently of one another
+ * (that is what the message snapshot is for), and elementwise loops have no order,
+ * so threads over ranks or elements change no operation and no operand.
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -76,13 +83,17 @@ int eso_ring_allreduce(float *buf, uint64_t L, uint32_t N, uint32_t A)
     for (int phase = 0; phase < 2; ++phase) {
         for (uint32_t s = 0; s + 1 < N; ++s) {
             /* every rank posts its message first ... */
+            #pragma omp parallel for schedule(static)
             for (uint32_t r = 0; r < N; ++r) {
+                uint64_t lo, hi;
                 uint32_t c = mod_n((int64_t)r - s + phase, N);
                 eso_chunk_bounds(L, N, A, c, &lo, &hi);
                 memcpy(msg + (size_t)r * cl, buf + (size_t)r * L + lo, (hi - lo) * sizeof(float));
             }
             /* ... then every rank consumes the message of its left neighbour */
+            #pragma omp parallel for schedule(static)
             for (uint32_t r = 0; r < N; ++r) {
+                uint64_t lo, hi;
                 uint32_t from = mod_n((int64_t)r - 1, N);
                 uint32_t c = mod_n((int64_t)from - s + phase, N);
                 eso_chunk_bounds(L, N, A, c, &lo, &hi);
@@ -113,10 +124,15 @@ int eso_ring_order_reduce(float *buf, uint64_t L, uint32_t N, uint32_t A, float 
     int rc = eso_ring_allreduce(buf, L, N, A);
     if (rc)
         return rc;
+    int differ = 0;
+    #pragma omp parallel for schedule(static) reduction(|:differ)
     for (uint32_t r = 1; r < N; ++r)
         if (memcmp(buf, buf + (size_t)r * L, L * sizeof(float)) != 0)
-            return -2;
+            differ |= 1;
+    if (differ)
+        return -2;
     float n = (float)N;
+    #pragma omp parallel for schedule(static)
     for (uint64_t i = 0; i < L; ++i)
         out[i] = buf[i] / n;
     return 0;
@@ -131,6 +147,7 @@ int eso_ring_order_reduce(float *buf, uint64_t L, uint32_t N, uint32_t A, float 
  */
 void eso_sgd_momentum(float *p, float *v, const float *g, uint64_t n, float lr, float mu)
 {
+    #pragma omp parallel for schedule(static)
     for (uint64_t i = 0; i < n; ++i) {
         float mv = mu * v[i];
         float vn = mv + g[i];

@@ -27,7 +27,15 @@ class EsBucketLayout(ctypes.Structure):
                 ("buckets", ctypes.POINTER(EsBucket)),
                 ("chunk_align", ctypes.c_uint32),
                 ("n_state_segs", ctypes.c_uint32),
-                ("state_seg_bytes", ctypes.POINTER(ctypes.c_uint64))]
+                ("state_seg_bytes", ctypes.POINTER(ctypes.c_uint64)),
+                ("dev_alloc", ctypes.c_void_p),
+                ("dev_free", ctypes.c_void_p),
+                ("user", ctypes.c_void_p)]
+
+
+# es_dev_alloc_fn / es_dev_free_fn of include/es.h
+DEV_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)
+DEV_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
 
 class EsTile(ctypes.Structure):
@@ -116,18 +124,20 @@ EXPORTS = tuple(_SIGS)
 
 
 def lib() -> ctypes.CDLL:
-    """The loaded libes.so.  Built first only if no built library exists."""
+    """The loaded libes.so.  It is built first if there is none or if the one there was built from
+    other sources than the tree holds; a library whose compiled-in source hash still differs
+    afterwards is refused."""
     global _lib
     if _lib is None:
-        path = os.environ.get("ES_LIB_PATH") or _build.LIB      # override: A/B runs of two builds
-        if not os.path.exists(path):
-            if path != _build.LIB:
-                raise FileNotFoundError(path)
-            _build.build(force=True)
-        L = ctypes.CDLL(path)
+        _build.build(force=False)
+        L = ctypes.CDLL(_build.LIB)
         for name, (res, args) in _SIGS.items():
             fn = getattr(L, name)          # AttributeError if a declared symbol is missing
             fn.restype, fn.argtypes = res, args
+        version, want = L.es_version().decode(), _build.source_hash()
+        if not version.endswith("src:" + want):
+            raise RuntimeError(f"{_build.LIB} is '{version}' but the sources hash to {want}: rebuild it "
+                               f"(python -m paper_2208_14228_amd.build)")
         _lib = L
     return _lib
 
@@ -142,11 +152,14 @@ def check(status: int, where: str, h: Optional[int] = None) -> int:
 # ---- thin wrappers: one per entry point, same names ---------------------------------
 
 def es_init(n_logical: int, n_params: int, buckets: Sequence[Tuple[int, int]], chunk_align: int,
-            state_seg_bytes: Sequence[int] = ()) -> Tuple[int, int]:
-    """Returns (status, handle)."""
+            state_seg_bytes: Sequence[int] = (), dev_alloc=None, dev_free=None) -> Tuple[int, int]:
+    """Returns (status, handle).  ``dev_alloc`` / ``dev_free`` are DEV_ALLOC_FN / DEV_FREE_FN objects
+    (or None for hipMalloc); the caller keeps them alive until es_destroy has returned."""
     arr = (EsBucket * max(1, len(buckets)))(*[EsBucket(o, l) for o, l in buckets])
     segs = (ctypes.c_uint64 * max(1, len(state_seg_bytes)))(*state_seg_bytes)
-    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs)
+    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs,
+                         ctypes.cast(dev_alloc, ctypes.c_void_p) if dev_alloc else None,
+                         ctypes.cast(dev_free, ctypes.c_void_p) if dev_free else None, None)
     h = _VP()
     st = lib().es_init(ctypes.byref(h), n_logical, ctypes.byref(lay))
     return st, (h.value or 0)
@@ -230,7 +243,7 @@ def es_get_option(h, name: str) -> Tuple[int, int]:
 def _layout(n_params, buckets, chunk_align, state_seg_bytes=()):
     arr = (EsBucket * max(1, len(buckets)))(*[EsBucket(o, l) for o, l in buckets])
     segs = (ctypes.c_uint64 * max(1, len(state_seg_bytes)))(*state_seg_bytes)
-    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs)
+    lay = EsBucketLayout(n_params, len(buckets), arr, chunk_align, len(state_seg_bytes), segs, None, None, None)
     lay._keep = (arr, segs)
     return lay
 

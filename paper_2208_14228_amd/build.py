@@ -1,6 +1,7 @@
 """Builds libes.so (HIP, gfx950 only) in-tree with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -9,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libes.so")
+STAMP = LIB + ".srchash"
 SOURCES = [os.path.join(CSRC, "es_kernels.hip"), os.path.join(CSRC, "es_api.cpp"),
            os.path.join(CSRC, "es_sched.cpp")]
 HEADERS = [os.path.join(CSRC, "es_internal.h"), os.path.join(ROOT, "include", "es.h"),
@@ -35,19 +37,34 @@ def hipcc() -> str:
     return "hipcc"
 
 
+def source_hash() -> str:
+    """Identifies what a library was built from: the sources, the headers and the flags."""
+    h = hashlib.sha256(" ".join(f for f in FLAGS if not os.path.isabs(f)).encode())
+    for f in SOURCES + HEADERS:
+        with open(f, "rb") as fh:
+            h.update(os.path.basename(f).encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
 def stale() -> bool:
-    if not os.path.exists(LIB):
+    """True if there is no built library, or it was built from other sources than the tree holds
+    (the hash of what it was built from sits beside it and is compiled into es_version())."""
+    try:
+        with open(STAMP) as fh:
+            return not os.path.exists(LIB) or fh.read().strip() != source_hash()
+    except OSError:
         return True
-    t = os.path.getmtime(LIB)
-    return any(os.path.getmtime(f) > t for f in SOURCES + HEADERS + [os.path.abspath(__file__)])
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
     if force or stale():
-        cmd = [hipcc(), *FLAGS, *SOURCES, "-o", LIB]
+        tag = source_hash()
+        cmd = [hipcc(), *FLAGS, f'-DES_SOURCE_HASH="{tag}"', *SOURCES, "-o", LIB]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
+        with open(STAMP, "w") as fh:
+            fh.write(tag + "\n")
     return LIB
 
 

@@ -52,7 +52,9 @@ struct es_handle {
     const float** d_slots = nullptr;            // N device pointers, by virtual rank
     float* d_partials = nullptr;                // ceil(P / 4096) block partials of es_grad_sq_norm
 
-    InPlace in_place{};                         // ESTs whose gradients the next reduce reads in place
+    // ESTs whose gradients the next reduce reads in place (rank, caller's flat gradient)
+    std::vector<uint32_t> in_place_rank;
+    std::vector<const float*> in_place_ptr;
     std::vector<uint8_t> accumulated;           // [est * n_buckets + bucket]
     uint64_t n_accumulated = 0;
 
@@ -66,6 +68,11 @@ struct es_handle {
     uint64_t hbm_grad_bytes = 0;                // HBM held by gradient arenas allocated in the current regrouping
     uint32_t tile_elems = 2048;
     ReduceShape shape{2, 8, 1, 0, 1, 0};
+
+    // the caller's device allocator (es_bucket_layout), or null: hipMalloc / hipFree
+    es_dev_alloc_fn dev_alloc = nullptr;
+    es_dev_free_fn dev_free = nullptr;
+    void* user = nullptr;
 
     int last_hip = 0;
 };
@@ -86,6 +93,27 @@ int hip_fail(es_handle* h, hipError_t e)
 
 uint64_t round_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
+// Device memory of the handle: the caller's allocator if one was given, else hipMalloc.
+hipError_t dev_malloc(es_handle* h, void** out, size_t bytes)
+{
+    if (!h->dev_alloc) return hipMalloc(out, bytes);
+    void* p = h->dev_alloc(bytes, h->user);
+    if (p && (((uintptr_t)p) & (kSlotAlignBytes - 1))) {       // the contract asks for 256-byte alignment
+        h->dev_free(p, h->user);
+        *out = nullptr;
+        return hipErrorInvalidValue;
+    }
+    *out = p;
+    return p ? hipSuccess : hipErrorOutOfMemory;
+}
+
+void dev_release(es_handle* h, void* p)
+{
+    if (!p) return;
+    if (h->dev_free) h->dev_free(p, h->user);
+    else (void)hipFree(p);
+}
+
 float* slot_base(const es_handle* h, uint32_t est)
 {
     const Worker& w = h->workers[h->worker_of[est]];
@@ -98,11 +126,14 @@ uint8_t* ctx_base(const es_handle* h, uint32_t est)
     return w.ctx_arena + (uint64_t)h->slot_of[est] * h->ctx_stride;
 }
 
-void free_worker(Worker& w)
+void free_worker(es_handle* h, Worker& w)
 {
-    if (w.grad_arena) (void)(w.grad_on_host ? hipHostFree(w.grad_arena) : hipFree(w.grad_arena));
-    if (w.ctx_arena) (void)hipFree(w.ctx_arena);
-    if (w.d_pieces) (void)hipFree(w.d_pieces);
+    if (w.grad_arena) {
+        if (w.grad_on_host) (void)hipHostFree(w.grad_arena);
+        else dev_release(h, w.grad_arena);
+    }
+    dev_release(h, w.ctx_arena);
+    dev_release(h, w.d_pieces);
     w = Worker{};
 }
 
@@ -119,11 +150,11 @@ int alloc_worker(es_handle* h, Worker& w, uint32_t n_slots)
         if (!w.grad_on_host) h->hbm_grad_bytes += gbytes;
         hipError_t e = w.grad_on_host
                            ? hipHostMalloc((void**)&w.grad_arena, gbytes, hipHostMallocMapped | hipHostMallocPortable)
-                           : hipMalloc((void**)&w.grad_arena, gbytes);
+                           : dev_malloc(h, (void**)&w.grad_arena, gbytes);
         if (e != hipSuccess) { h->last_hip = (int)e; w.grad_arena = nullptr; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
     }
     if (cbytes) {
-        hipError_t e = hipMalloc((void**)&w.ctx_arena, cbytes);
+        hipError_t e = dev_malloc(h, (void**)&w.ctx_arena, cbytes);
         if (e != hipSuccess) { h->last_hip = (int)e; return e == hipErrorOutOfMemory ? ES_ENOMEM : ES_EHIP; }
         e = hipMemset(w.ctx_arena, 0, cbytes);
         if (e != hipSuccess) return hip_fail(h, e);
@@ -190,10 +221,10 @@ int build_tiles(es_handle* h)
     h->n_big = (uint32_t)big.size();
     big.insert(big.end(), tiles.begin(), tiles.end());
     tiles.swap(big);
-    if (h->d_tiles) { (void)hipFree(h->d_tiles); h->d_tiles = nullptr; }
+    if (h->d_tiles) { dev_release(h, h->d_tiles); h->d_tiles = nullptr; }
     h->n_tiles = (uint32_t)tiles.size();
     if (h->n_tiles) {
-        ES_HIP(h, hipMalloc((void**)&h->d_tiles, tiles.size() * sizeof(Tile)));
+        ES_HIP(h, dev_malloc(h, (void**)&h->d_tiles, tiles.size() * sizeof(Tile)));
         ES_HIP(h, hipMemcpy(h->d_tiles, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
     }
     return ES_OK;
@@ -204,6 +235,7 @@ int validate_layout(uint32_t n_logical, const es_bucket_layout* lay)
     if (!lay || n_logical == 0 || n_logical > 65535) return ES_EINVAL;
     if (lay->chunk_align == 0 || (lay->n_buckets && !lay->buckets)) return ES_EINVAL;
     if (lay->n_state_segs && !lay->state_seg_bytes) return ES_EINVAL;
+    if ((lay->dev_alloc == nullptr) != (lay->dev_free == nullptr)) return ES_EINVAL;   // both or neither
     uint64_t pos = 0;
     for (uint32_t b = 0; b < lay->n_buckets; ++b) {
         if (lay->buckets[b].offset_elems != pos) return ES_EINVAL;        // ascending, disjoint, no gaps
@@ -220,7 +252,7 @@ int upload_slot_table(es_handle* h)
 {
     std::vector<const float*> ptrs(h->N);
     for (uint32_t e = 0; e < h->N; ++e) ptrs[e] = slot_base(h, e);
-    if (!h->d_slots) ES_HIP(h, hipMalloc((void**)&h->d_slots, h->N * sizeof(float*)));
+    if (!h->d_slots) ES_HIP(h, dev_malloc(h, (void**)&h->d_slots, h->N * sizeof(float*)));
     ES_HIP(h, hipMemcpy((void*)h->d_slots, ptrs.data(), h->N * sizeof(float*), hipMemcpyHostToDevice));
     return ES_OK;
 }
@@ -319,6 +351,9 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
         h->N = n_logical;
         h->P = lay->n_params;
         h->A = lay->chunk_align;
+        h->dev_alloc = lay->dev_alloc;
+        h->dev_free = lay->dev_free;
+        h->user = lay->user;
         h->buckets.assign(lay->buckets, lay->buckets + lay->n_buckets);
         uint64_t off = 0;
         for (uint32_t j = 0; j < lay->n_state_segs; ++j) {
@@ -359,7 +394,7 @@ int es_init(es_handle** out, uint32_t n_logical, const es_bucket_layout* lay)
     if (rc == ES_OK) rc = build_tiles(h);
     if (rc == ES_OK) rc = upload_slot_table(h);
     if (rc == ES_OK && h->P) {
-        e = hipMalloc((void**)&h->d_partials, ((h->P + 4095) / 4096) * sizeof(float));
+        e = dev_malloc(h, (void**)&h->d_partials, ((h->P + 4095) / 4096) * sizeof(float));
         if (e != hipSuccess) rc = hip_fail(h, e);
     }
     if (rc != ES_OK) { es_destroy(h); return rc; }
@@ -374,10 +409,10 @@ int es_destroy(es_handle* h)
     (void)hipStreamSynchronize(h->s_main);
     (void)hipStreamSynchronize(h->s_ctx);
     (void)hipStreamSynchronize(h->s_stage);
-    for (Worker& w : h->workers) free_worker(w);
-    if (h->d_tiles) (void)hipFree(h->d_tiles);
-    if (h->d_slots) (void)hipFree((void*)h->d_slots);
-    if (h->d_partials) (void)hipFree(h->d_partials);
+    for (Worker& w : h->workers) free_worker(h, w);
+    dev_release(h, h->d_tiles);
+    dev_release(h, (void*)h->d_slots);
+    dev_release(h, h->d_partials);
     if (h->ev_main) (void)hipEventDestroy(h->ev_main);
     if (h->ev_ctx) (void)hipEventDestroy(h->ev_ctx);
     if (h->ev_stage) (void)hipEventDestroy(h->ev_stage);
@@ -439,6 +474,7 @@ try {
     if (rc != ES_OK) return rc;
 
     std::vector<Worker> fresh(n_workers);
+    const uint64_t hbm_before = h->hbm_grad_bytes;
     h->hbm_grad_bytes = 0;                       // placement is decided anew, worker by worker
     for (uint32_t w = 0; w < n_workers && rc == ES_OK; ++w) {
         fresh[w].live.assign(h->seg_bytes.size(), nullptr);
@@ -457,10 +493,11 @@ try {
         }
     }
     if (rc != ES_OK) {
-        for (Worker& w : fresh) free_worker(w);
+        for (Worker& w : fresh) free_worker(h, w);
+        h->hbm_grad_bytes = hbm_before;          // the previous grouping stays in force, with its placement
         return rc;
     }
-    for (Worker& w : h->workers) free_worker(w);
+    for (Worker& w : h->workers) free_worker(h, w);
     h->workers.swap(fresh);
     h->worker_of.assign(worker_of_est, worker_of_est + h->N);
     h->slot_of.assign(slot_of_est, slot_of_est + h->N);
@@ -502,9 +539,9 @@ try {
     // the worker counts as unbound until the new table is in place
     w.bound = false;
     w.n_pieces = 0;
-    if (w.d_pieces) { (void)hipFree(w.d_pieces); w.d_pieces = nullptr; }
+    if (w.d_pieces) { dev_release(h, w.d_pieces); w.d_pieces = nullptr; }
     if (!pieces.empty()) {
-        ES_HIP(h, hipMalloc((void**)&w.d_pieces, pieces.size() * sizeof(Piece)));
+        ES_HIP(h, dev_malloc(h, (void**)&w.d_pieces, pieces.size() * sizeof(Piece)));
         ES_HIP(h, hipMemcpy(w.d_pieces, pieces.data(), pieces.size() * sizeof(Piece), hipMemcpyHostToDevice));
     }
     w.n_pieces = (uint32_t)pieces.size();
@@ -589,10 +626,13 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
     DeviceGuard guard__(h);
     const size_t nb = h->buckets.size();
     // validate everything first: a failing call must enqueue nothing and mark nothing
+    uint64_t blocks_bound = 0;               // workgroups of the whole batch: a bound on every launch's grid
     for (uint32_t k = 0; k < n; ++k) {
         const uint32_t b = buckets[k];
         if (b >= nb) return ES_EINVAL;
         const uint64_t len = h->buckets[b].len_elems;
+        blocks_bound += ((len >> 2) + kCopyBlock - 1) / kCopyBlock + 1;
+        if (blocks_bound > 0x7fffffffull) return ES_EINVAL;
         const float* src = d_grad_buckets[k];
         if (len && (!src || (((uintptr_t)src) & 3))) return ES_EINVAL;
         for (uint32_t j = 0; j < k; ++j)
@@ -644,7 +684,6 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
             const uint64_t vec = runs.n[nr - 1] >> 2;
             uint64_t blocks = (vec + kCopyBlock - 1) / kCopyBlock;
             if (blocks == 0) blocks = 1;
-            if (runs.first_block[nr - 1] + blocks > 0x7fffffffull) return ES_EINVAL;
             runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;
             h->stage_pending = true;
         }
@@ -655,19 +694,19 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
 }
 
 int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad)
-{
+try {
     if (!h || est >= h->N) return ES_EINVAL;
     if (h->P && (!d_flat_grad || !aligned16(d_flat_grad))) return ES_EINVAL;
     const size_t nb = h->buckets.size();
     for (size_t b = 0; b < nb; ++b)
         if (h->accumulated[(size_t)est * nb + b]) return ES_ESTATE;
-    if (h->in_place.n == kMaxInPlace) return ES_ESTATE;
-    h->in_place.rank[h->in_place.n] = est;
-    h->in_place.ptr[h->in_place.n] = d_flat_grad;
-    h->in_place.n++;
+    h->in_place_rank.push_back(est);
+    h->in_place_ptr.push_back(d_flat_grad);
     for (size_t b = 0; b < nb; ++b) h->accumulated[(size_t)est * nb + b] = 1;
     h->n_accumulated += nb;
     return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
 }
 
 int es_stage_fence(es_handle* h)
@@ -694,12 +733,30 @@ int es_dropout_mask(es_handle* h, uint32_t est, uint32_t state_seg, uint8_t* d_m
     return ES_OK;
 }
 
+// Redirects the table entries of the ESTs taken in place, kMaxInPlace per launch: to the
+// caller's gradients, or back to the ESTs' own slots.
+static hipError_t patch_table(es_handle* h, bool to_caller)
+{
+    const size_t n = h->in_place_rank.size();
+    for (size_t k0 = 0; k0 < n; k0 += kMaxInPlace) {
+        InPlace patch{};
+        patch.n = (uint32_t)std::min<size_t>(kMaxInPlace, n - k0);
+        for (uint32_t k = 0; k < patch.n; ++k) {
+            patch.rank[k] = h->in_place_rank[k0 + k];
+            patch.ptr[k] = to_caller ? h->in_place_ptr[k0 + k] : slot_base(h, patch.rank[k]);
+        }
+        const hipError_t e = launch_patch_slots(h->s_main, h->d_slots, patch);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr, float mu)
 {
     if (h->n_accumulated != (uint64_t)h->N * h->buckets.size()) return ES_ESTATE;
     // gradients taken in place must not overlap what this launch writes
-    for (uint32_t k = 0; k < h->in_place.n; ++k) {
-        const uintptr_t g = (uintptr_t)h->in_place.ptr[k], sz = h->P * sizeof(float);
+    for (size_t k = 0; k < h->in_place_ptr.size(); ++k) {
+        const uintptr_t g = (uintptr_t)h->in_place_ptr[k], sz = h->P * sizeof(float);
         for (const float* o : {(const float*)avg, (const float*)p, (const float*)v}) {
             const uintptr_t b = (uintptr_t)o;
             if (o && g < b + sz && b < g + sz) return ES_EINVAL;
@@ -707,19 +764,21 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     }
     int rc = es_stage_fence(h);
     if (rc != ES_OK) return rc;
-    // gradients taken in place: point their ranks at caller memory for this launch only
-    ES_HIP(h, launch_patch_slots(h->s_main, h->d_slots, h->in_place));
-    const hipError_t launched = launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N,
-                                                   avg, p, v, lr, mu, h->shape);
-    if (h->in_place.n) {                         // the table goes back to the slots whether or not the launch worked
-        for (uint32_t k = 0; k < h->in_place.n; ++k) h->in_place.ptr[k] = slot_base(h, h->in_place.rank[k]);
-        const hipError_t restored = launch_patch_slots(h->s_main, h->d_slots, h->in_place);
-        if (launched == hipSuccess) ES_HIP(h, restored);
-    }
-    ES_HIP(h, launched);
+    // gradients taken in place: point their ranks at caller memory for this launch only, then
+    // back at the slots, whether or not the launches in between worked.  The handle's record
+    // of the caller's pointers is left as it is until the whole step has been enqueued, so a
+    // reduce that failed can be called again and reads the same gradients.
+    hipError_t status = patch_table(h, /*to_caller=*/true);
+    if (status == hipSuccess)
+        status = launch_ring_reduce(h->s_main, h->d_tiles, h->n_tiles, h->n_big, h->d_slots, h->N,
+                                    avg, p, v, lr, mu, h->shape);
+    const hipError_t restored = patch_table(h, /*to_caller=*/false);
+    ES_HIP(h, status);
+    ES_HIP(h, restored);
     std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
     h->n_accumulated = 0;
-    h->in_place.n = 0;
+    h->in_place_rank.clear();
+    h->in_place_ptr.clear();
     return ES_OK;
 }
 
@@ -972,6 +1031,9 @@ const char* es_strerror(int status)
     }
 }
 
-const char* es_version(void) { return "libes 0.1 (gfx950)"; }
+#ifndef ES_SOURCE_HASH
+#define ES_SOURCE_HASH "unknown"
+#endif
+const char* es_version(void) { return "libes 0.2 (gfx950) src:" ES_SOURCE_HASH; }
 
 }  // extern "C"

@@ -38,7 +38,7 @@ constexpr uint32_t kCopyBlock = ES_COPY_BLOCK;   // lanes per workgroup of the b
 
 // Entries of the rank -> gradient-base table that are redirected for one reduce
 // (gradients taken in place from caller memory, no staging copy).
-constexpr uint32_t kMaxInPlace = 8;
+constexpr uint32_t kMaxInPlace = 16;            // entries one patch launch carries
 struct InPlace {
     uint32_t     n;
     uint32_t     rank[kMaxInPlace];

@@ -231,6 +231,8 @@ try {
         combos *= (uint64_t)available[i] + 1;
         if (combos > (1ull << 20)) return ES_EINVAL;
     }
+    // one best-mapping search per count vector costs on the order of max_p steps: bound the product
+    if (combos * (uint64_t)max_p > (1ull << 27)) return ES_EINVAL;
     Problem pr;
     pr.K = n_types; pr.C = capability; pr.max_p = max_p;
     std::vector<es_sched_plan> best;                  // ranked, at most top_k entries

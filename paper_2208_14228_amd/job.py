@@ -13,12 +13,38 @@ import torch
 from . import binding as B
 
 
+class TorchDeviceMemory:
+    """The library's device memory taken from torch's caching allocator (the allocator callbacks
+    of es_bucket_layout): every block is a uint8 tensor that lives until the library frees it."""
+
+    def __init__(self, device):
+        self.device = device
+        self.blocks = {}
+        self.alloc_fn = B.DEV_ALLOC_FN(self._alloc)
+        self.free_fn = B.DEV_FREE_FN(self._free)
+
+    def _alloc(self, nbytes, _user):
+        try:
+            t = torch.empty(max(int(nbytes), 1), dtype=torch.uint8, device=self.device)
+        except Exception:               # out of memory: the library reports ES_ENOMEM
+            return None
+        self.blocks[t.data_ptr()] = t
+        return t.data_ptr()
+
+    def _free(self, ptr, _user):
+        self.blocks.pop(ptr, None)
+
+    @property
+    def nbytes(self):
+        return sum(t.numel() for t in self.blocks.values())
+
+
 class ESTJob:
     def __init__(self, n_logical: int, n_params: int, buckets: Sequence[Tuple[int, int]],
                  chunk_align: int, state_seg_bytes: Sequence[int] = (),
                  worker_of_est: Optional[Sequence[int]] = None,
                  slot_of_est: Optional[Sequence[int]] = None,
-                 device: str = "cuda:0", use_streams=True, live_alloc=None):
+                 device: str = "cuda:0", use_streams=True, live_alloc=None, torch_memory=True):
         if not torch.cuda.is_available():
             raise RuntimeError("ESTJob needs a GPU: libes has no CPU path")
         self.device = torch.device(device)
@@ -27,11 +53,17 @@ class ESTJob:
         self.P = n_params
         self.buckets = list(buckets)
         self.seg_bytes = list(state_seg_bytes)
-        st, self.h = B.es_init(n_logical, n_params, self.buckets, chunk_align, self.seg_bytes)
+        # torch owns the device memory of the job (gradient slots included) unless told otherwise
+        self.memory = TorchDeviceMemory(self.device) if torch_memory else None
+        st, self.h = B.es_init(n_logical, n_params, self.buckets, chunk_align, self.seg_bytes,
+                               self.memory.alloc_fn if self.memory else None,
+                               self.memory.free_fn if self.memory else None)
         B.check(st, "es_init")
         self.worker_of = list(worker_of_est) if worker_of_est is not None else [0] * n_logical
         self.slot_of = list(slot_of_est) if slot_of_est is not None else list(range(n_logical))
-        if worker_of_est is not None:
+        # es_init starts with one worker that holds every EST in rank order: only another grouping
+        # needs a regrouping (which holds both sets of gradient slots while it runs)
+        if self.worker_of != [0] * n_logical or self.slot_of != list(range(n_logical)):
             B.check(B.es_set_grouping(self.h, self.worker_of, self.slot_of), "es_set_grouping", self.h)
         self.main = self.ctx = self.stage = None
         # use_streams: True / "three" = separate main, ctx and stage streams (staging and context

@@ -40,7 +40,7 @@ int main(void)
     const uint64_t P = 3 * 4096 + 37 + 1001 + 40000;
     const uint32_t A = 4;
     const float lr = 0.1f, mu = 0.9f;
-    es_bucket_layout lay = { P, NB, buckets, A, 0, NULL };
+    es_bucket_layout lay = { P, NB, buckets, A, 0, NULL, NULL, NULL, NULL };
 
     es_handle *h = NULL;
     ES(es_init(&h, N, &lay));

@@ -39,7 +39,7 @@ int main()
                         es_bucket b[4];
                         uint64_t off = 0;
                         for (int k = 0; k < 4; ++k) { b[k] = {off, l[k]}; off += l[k]; }
-                        es_bucket_layout lay = {off, 4, b, A, 0, nullptr};
+                        es_bucket_layout lay = {off, 4, b, A, 0, nullptr, nullptr, nullptr, nullptr};
                         uint64_t nt = 0, nb = 0;
                         CHECK(es_plan_tiles(N, &lay, tile, big, nullptr, 0, &nt, &nb) == ES_OK);
                         std::vector<es_tile> t(nt + 1);
@@ -53,7 +53,7 @@ int main()
     // argument validation never touches memory it was not given
     es_handle* h = nullptr;
     es_bucket one = {0, 8}, gap[2] = {{0, 4}, {5, 3}};
-    es_bucket_layout ok = {8, 1, &one, 1, 0, nullptr}, bad = {8, 2, gap, 1, 0, nullptr};
+    es_bucket_layout ok = {8, 1, &one, 1, 0, nullptr, nullptr, nullptr, nullptr}, bad = {8, 2, gap, 1, 0, nullptr, nullptr, nullptr, nullptr};
     CHECK(es_init(nullptr, 2, &ok) == ES_EINVAL);
     CHECK(es_init(&h, 0, &ok) == ES_EINVAL && h == nullptr);
     CHECK(es_init(&h, 2, &bad) == ES_EINVAL && h == nullptr);

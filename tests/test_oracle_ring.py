@@ -235,3 +235,31 @@ def test_random_geometries_against_closed_form():
             assert bits(got[i:i + 1])[0] == bits(np.array([acc / np.float32(N)]))[0]
 
     prop()
+
+
+def test_all_core_build_of_the_oracle_gives_the_same_bits():
+    """bench.py also times es_oracle.c built with -fopenmp (threads over the ring's ranks and over
+    elementwise loops).  It must be the same function: compared here with the pinned default
+    build on ragged geometries, and switched back afterwards."""
+    rng = np.random.default_rng(77)
+    cases = [(N, L, A) for N in (1, 2, 3, 5, 8, 17) for L in (0, 1, 7, 64, 1001, 40_003) for A in (1, 4)]
+    want = {}
+    for N, L, A in cases:
+        g = (rng.standard_normal((N, L)) * np.exp2(rng.integers(-20, 20, (N, L)))).astype(np.float32)
+        want[(N, L, A)] = (g, oracle.ring_order_reduce(g, A))
+    p0 = rng.standard_normal(5003).astype(np.float32)
+    v0 = rng.standard_normal(5003).astype(np.float32)
+    gr = rng.standard_normal(5003).astype(np.float32)
+    p1, v1 = p0.copy(), v0.copy()
+    oracle.sgd_momentum(p1, v1, gr, 0.1, 0.9)
+    oracle.use_all_cores(True)
+    try:
+        for key, (g, ref) in want.items():
+            got = oracle.ring_order_reduce(g, key[2])
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), key
+        p2, v2 = p0.copy(), v0.copy()
+        oracle.sgd_momentum(p2, v2, gr, 0.1, 0.9)
+        assert np.array_equal(p1.view(np.uint32), p2.view(np.uint32))
+        assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+    finally:
+        oracle.use_all_cores(False)
