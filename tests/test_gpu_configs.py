@@ -1,13 +1,18 @@
 """The five benchmark configurations at full size, in the launch configuration bench.py times.
 
+Every output element of every configuration is compared with the CPU oracle.
 Configurations 1, 2 and 4 are small enough for the message-passing oracle to
-replay the whole job on the host: every output element is compared.  For
-configurations 3 and 5 the oracle replays (a) sampled windows of every bucket
-through the closed-form fold - around every ring-chunk boundary, at the bucket
-edges and at seeded random places - across all global steps, (b) a few whole
-buckets through the ring simulator, and (c) every dropout mask and RNG state.
-All groupings of a configuration must agree with each other over the *whole*
-vectors (compared on the device)."""
+replay the whole job on the host in one go.  Configurations 3 and 5 are
+streamed: after every global step the N gradient rows of one bucket at a time
+are generated again, copied into a pinned host buffer and run through the ring
+simulator; the averaged gradient of that bucket is compared with the device's,
+then the oracle's SGD-momentum update is applied to the host copy of that
+bucket's parameters and momentum, which are compared in full after the last
+step (3 steps for configuration 3, 2 for configuration 5, so momentum carried
+over from an earlier step enters the update).  One bucket per step also goes
+through the closed-form fold.  Every dropout mask and RNG state is replayed.
+The other groupings, and the launch configuration bench.py times, must then
+reproduce the first grouping's vectors bit for bit (compared on the device)."""
 from typing import Dict, List, Tuple
 
 import numpy as np
@@ -61,124 +66,83 @@ def bench_launch_configuration(sc, g, want_p, want_v):
         job.close()
 
 
-def windows_for(sc: S.Scenario, n_random: int, seed: int) -> List[Tuple[int, int, int]]:
-    """(bucket, lo, hi) bucket-local windows: chunk boundaries, bucket edges, random places."""
-    rng = np.random.default_rng(seed)
-    N, A = sc.n_logical, sc.chunk_align
-    out = []
-    for b, (_, L) in enumerate(sc.layout.buckets):
+def streamed_oracle_step(sc, job, t, pin, host_p, host_v, what):
+    """Global step t of the whole job on the host, one bucket at a time, against the device's
+    averaged gradient; updates host_p / host_v with the oracle's SGD-momentum."""
+    N = sc.n_logical
+    for b, (off, L) in enumerate(sc.layout.buckets):
         if L == 0:
             continue
-        marks = {0, L}
-        cl = fold_def.chunk_len(L, N, A)
-        marks |= {min(L, c * cl) for c in range(N + 1)}
-        marks |= {int(x) for x in rng.integers(0, L, size=n_random)}
-        for m in sorted(marks):
-            lo, hi = max(0, m - 48), min(L, m + 48)
-            if lo < hi:
-                out.append((b, lo, hi))
-    return out
+        rows = pin[:N * L].view(N, L)
+        for r in range(N):             # seeded inputs, evaluated by torch on the device
+            rows[r].copy_(S.grad(sc, t, r, b, G.DEV), non_blocking=True)
+        torch.cuda.synchronize()
+        ranks = rows.numpy()
+        closed_form = fold_def.fold_reduce(ranks, sc.chunk_align) if b == t % sc.layout.n_buckets else None
+        want = oracle.ring_order_reduce(ranks, sc.chunk_align, clobber=True)
+        if closed_form is not None:
+            assert np.array_equal(bits(closed_form), bits(want)), (what, "simulator vs closed form", t, b)
+        got = job.avg[off:off + L].cpu().numpy()
+        assert np.array_equal(bits(got), bits(want)), (what, "averaged gradient", "step", t, "bucket", b)
+        oracle.sgd_momentum(host_p[off:off + L], host_v[off:off + L], want, sc.lr, sc.momentum)
+    print(f"[oracle] {what}: step {t} checked on all {sc.layout.n_buckets} buckets", flush=True)
 
 
-def windowed_reference(sc: S.Scenario, wins) -> Dict[Tuple[int, int, int], Tuple[np.ndarray, ...]]:
-    """avg (last step), p, v after sc.steps steps on the windows only."""
-    res = {}
-    N = sc.n_logical
-    by_bucket: Dict[int, List[Tuple[int, int]]] = {}
-    for (b, lo, hi) in wins:
-        by_bucket.setdefault(b, []).append((lo, hi))
-    for b, ws in by_bucket.items():
-        off, L = sc.layout.buckets[b]
-        idx = torch.cat([torch.arange(off + lo, off + hi, dtype=torch.int64) for lo, hi in ws])
-        starts = np.cumsum([0] + [hi - lo for lo, hi in ws])
-        p_all = synth.values_at(sc.layout, idx, sc.seed, 0, synth.STREAM_PARAM, 1.0, True).numpy().copy()
-        v_all = np.zeros_like(p_all)
-        avg_all = np.zeros_like(p_all)
-        for t in range(sc.steps):
-            g = np.stack([synth.values_at(sc.layout, idx, sc.seed, t, r).numpy() for r in range(N)])
-            for k, (lo, hi) in enumerate(ws):
-                s0 = starts[k]
-                fetch = lambda r, a, c: g[r, s0 + (a - lo):s0 + (c - lo)]
-                avg_all[s0:s0 + hi - lo] = fold_def.fold_window(fetch, lo, hi, L, N, sc.chunk_align)
-            oracle.sgd_momentum(p_all, v_all, avg_all, sc.lr, sc.momentum)
-        for k, (lo, hi) in enumerate(ws):
-            sl = slice(starts[k], starts[k + 1])
-            res[(b, lo, hi)] = (avg_all[sl].copy(), p_all[sl].copy(), v_all[sl].copy())
-    return res
-
-
-def check_windows(sc, job, wins, ref, what):
-    for (b, lo, hi) in wins:
-        off = sc.layout.buckets[b][0]
-        avg, p, v = ref[(b, lo, hi)]
-        sl = slice(off + lo, off + hi)
-        for name, dev_t, want in (("avg", job.avg, avg), ("p", job.p, p), ("v", job.v, v)):
-            got = dev_t[sl].cpu().numpy()
-            assert np.array_equal(bits(got), bits(want)), (what, name, b, lo, hi)
-
-
-def whole_bucket_check(sc, job, b, t_last, what):
-    """One whole bucket of the last step through the ring simulator."""
-    off, L = sc.layout.buckets[b]
-    ranks = np.empty((sc.n_logical, L), dtype=np.float32)
-    for r in range(sc.n_logical):             # seeded inputs, evaluated by torch on the device
-        ranks[r] = S.grad(sc, t_last, r, b, G.DEV).cpu().numpy()
-    want = oracle.ring_order_reduce(ranks, sc.chunk_align, clobber=True)
-    got = job.avg[off:off + L].cpu().numpy()
-    assert np.array_equal(bits(got), bits(want)), (what, "whole bucket", b)
-
-
-def run_sampled(cid: int, steps: int, n_random: int, whole_buckets, sync_each_est: bool):
+def run_streamed(cid: int, steps: int):
     cfg = configs.config(cid)
     sc = S.from_config(cfg, steps=steps)
-    wins = windows_for(sc, n_random, cid)
-    ref = windowed_reference(sc, wins)
+    N = sc.n_logical
+    pin = torch.empty(N * max(L for _, L in sc.layout.buckets), dtype=torch.float32, pin_memory=True)
     # the per-rank state (RNG states, masks) is cheap to replay in full on the host
     want_masks, want_philox = {}, None
     if sc.mask_n:
-        want_philox = np.array([[S.philox_seed(sc, e), 0] for e in range(sc.n_logical)], dtype=np.uint64)
+        want_philox = np.array([[S.philox_seed(sc, e), 0] for e in range(N)], dtype=np.uint64)
         for t in range(steps):
-            for e in range(sc.n_logical):
+            for e in range(N):
                 want_masks[(t, e)] = S.digest(oracle.dropout_mask(want_philox[e], sc.mask_n, sc.p_drop))
     keep = None
     for gi, g in enumerate(cfg.groupings):
         what = f"config {cid} grouping {g.name}"
-        print(f"[gpu-run] {what} steps={steps} windows={len(wins)}", flush=True)
+        print(f"[gpu-run] {what} steps={steps}", flush=True)
         job = G.make_job(sc, g)
         try:
             G.init_contexts(sc, job)
             masks = {}
-            G.run_steps(sc, job, g, fused=bool(gi % 2), use_switch=bool(gi % 2),
-                        sync_each_est=sync_each_est, masks=masks)
-            check_windows(sc, job, wins, ref, what)
             if gi == 0:
-                for b in whole_buckets:
-                    whole_bucket_check(sc, job, b, steps - 1, what)
+                host_p = synth.params(sc.layout, sc.seed, G.DEV).cpu().numpy()
+                host_v = np.zeros_like(host_p)
+                for t in range(steps):          # unfused here, so that every step's average is stored
+                    G.run_steps(sc, job, g, fused=False, use_switch=False, sync_each_est=True,
+                                masks=masks, steps=[t])
+                    streamed_oracle_step(sc, job, t, pin, host_p, host_v, what)
+                assert np.array_equal(bits(job.p.cpu().numpy()), bits(host_p)), (what, "parameters")
+                assert np.array_equal(bits(job.v.cpu().numpy()), bits(host_v)), (what, "momentum")
+                del host_p, host_v
+            else:
+                G.run_steps(sc, job, g, fused=bool(gi % 2), use_switch=bool(gi % 2),
+                            sync_each_est=True, masks=masks)
             if sc.mask_n:
                 assert masks == want_masks, what
                 got = G.collect(sc, job, masks)
                 assert np.array_equal(got.philox, want_philox), what
             cur = (job.avg.clone(), job.p.clone(), job.v.clone())
-            if gi == 0:
-                p_first, v_first = cur[1], cur[2]
             if keep is None:
                 keep = cur
-            else:                       # groupings agree over the whole vectors
+            else:                       # the other groupings reproduce the vectors the oracle has checked
                 for x, y, name in zip(keep, cur, ("avg", "p", "v")):
                     assert dev_bits_equal(x, y), (what, name)
         finally:
             job.close()
         torch.cuda.empty_cache()
-    # the windows and whole buckets above pin the first run to the oracle; the launch
-    # configuration bench.py times has to reproduce that run over the whole vectors
-    bench_launch_configuration(sc, cfg.groupings[0], p_first, v_first)
+    # ... and so does the launch configuration bench.py times
+    bench_launch_configuration(sc, cfg.groupings[0], keep[1], keep[2])
 
 
 def test_config3_bert_base_with_philox_context():
-    # 13 buckets; the 93 MiB embedding bucket (index 12) and a regular one go through the ring simulator
-    run_sampled(3, steps=2, n_random=6, whole_buckets=[0, 12], sync_each_est=True)
+    # 16 ranks x 13 buckets (one of them the 93 MiB embedding), 3 global steps, all through the ring simulator
+    run_streamed(3, steps=3)
 
 
 def test_config5_gpt2_medium_uneven_groupings():
-    # 64 ranks x 355M parameters: 90.8 GB of gradient slots on the device
-    run_sampled(5, steps=1, n_random=4, whole_buckets=[0], sync_each_est=True)
+    # 64 ranks x 355M parameters: 90.8 GB of gradient slots on the device, 2 global steps
+    run_streamed(5, steps=2)
