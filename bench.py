@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--split", action="store_true", help="reduce and SGD as two kernels")
     ap.add_argument("--per-bucket", action="store_true",
                     help="stage with one es_accumulate launch per bucket instead of es_accumulate_batch")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="an EST boundary as two launches (es_ctx_switch, then es_accumulate_batch) instead of "
+                         "the single es_est_boundary launch")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle legs (no zero_ulp either)")
     ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
     ap.add_argument("--no-extras", action="store_true",
@@ -312,6 +315,8 @@ def measure(torch, a, cid, headline, oracle_leg):
     fused = not a.split
     all_buckets = list(range(lay.n_buckets))
     src_ptrs = [[src[e].data_ptr() + 4 * off for off, _ in lay.buckets] for e in range(N)]
+    marshalled = [B.Marshalled(all_buckets, src_ptrs[e]) for e in range(N)]
+    one_launch = not (a.per_bucket or a.separate_calls)
 
     def events(n):
         return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -326,16 +331,18 @@ def measure(torch, a, cid, headline, oracle_leg):
     last_of_worker = [e for k, e in enumerate(sched)
                       if k + 1 == len(sched) or g.worker_of_est[sched[k + 1]] != g.worker_of_est[e]]
 
-    def enter(e):
+    next_of = {p: e for e, p in prev_of.items() if p is not None}
+
+    def enter(e, fused_boundary=False):
         if not segs:
             return
         if prev_of[e] is None:
             job.ctx_restore(e)
-        else:
+        elif not fused_boundary:              # else the previous EST's boundary launch has switched it in
             job.ctx_switch(prev_of[e], e)
 
-    def leave():
-        if segs:
+    def leave(fused_boundary=False):
+        if segs and not fused_boundary:       # else each worker's last boundary launch has saved it
             for e in last_of_worker:
                 job.ctx_save(e)
 
@@ -363,15 +370,17 @@ def measure(torch, a, cid, headline, oracle_leg):
                 job.stage.wait_stream(job.main)  # the interval below must not include the previous reduce
             ev_c[i][0].record(job.stage)
         for e in sched:
-            enter(e)
+            enter(e, one_launch)
             if mask is not None:
                 job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
-            if a.per_bucket:
+            if one_launch:                    # stage e, save e, restore the worker's next EST: one launch
+                B.es_est_boundary_m(job.h, e, next_of.get(e), marshalled[e])
+            elif a.per_bucket:
                 for b, (off, ln) in enumerate(lay.buckets):
                     B.es_accumulate(job.h, e, b, src[e].data_ptr() + 4 * off)
             else:
-                B.es_accumulate_batch(job.h, e, all_buckets, src_ptrs[e])
-        leave()
+                B.es_accumulate_batch_m(job.h, e, marshalled[e])
+        leave(one_launch)
         finish(i)
 
     # ---- one step on the GPU from (p0, v = 0), kept for the bit check against the oracle ----
@@ -445,10 +454,12 @@ def measure(torch, a, cid, headline, oracle_leg):
                    "memory": ("Infinity-Cache-assisted: parameters and momentum (4 of the N+4 units) are left "
                               "cacheable and can come back from the 256 MB cache, not from HBM"
                               if pv_cacheable else "all units stream from and to HBM")},
-        "staging": {"kernel": "k_copy_f4" if a.per_bucket else "k_copy_runs",
+        "staging": {"kernel": "k_copy_f4" if a.per_bucket else ("k_est_boundary" if one_launch else "k_copy_runs"),
                     "launches_per_step": N * sum(1 for _, ln in lay.buckets if ln) if a.per_bucket else N,
                     "bytes_per_step": bytes_stage, "stream_ms_per_step": stats_ms(stg),
-                    "includes": "the per-EST context switches and dropout masks enqueued between the copies",
+                    "includes": ("each launch also saves the EST's small state and restores the next EST's; "
+                                 if one_launch else "the per-EST context switches are launches of their own "
+                                 "between the copies; ") + "the dropout-mask launches sit between the copies too",
                     "achieved": round(bytes_stage / (stage_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                     "frac": round(bytes_stage / (stage_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)},
         "context_bytes_per_est": ctx_bytes, "mask_bytes_per_est": mask.numel() if mask is not None else 0,
@@ -462,6 +473,7 @@ def measure(torch, a, cid, headline, oracle_leg):
     # ---- the reduce with nothing in the Infinity Cache: a 1 GiB fill sweeps the cache before every
     # launch.  Only where parameters and momentum would fit it; both cache policies. ----
     slot_ptrs = [[B.es_grad_slot(job.h, e, b) for b in all_buckets] for e in range(N)]
+    slot_m = [B.Marshalled(all_buckets, slot_ptrs[e]) for e in range(N)]
     if fused and 2 * 4 * P <= CACHE_FIT_BYTES and not a.host_slots:
         sweep = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         cold = {}
@@ -470,7 +482,7 @@ def measure(torch, a, cid, headline, oracle_leg):
             ev = events(steps)
             for i in range(-2, steps):
                 for e in sched:                                   # gradients stay where they are in the slots
-                    B.es_accumulate_batch(job.h, e, all_buckets, slot_ptrs[e])
+                    B.es_accumulate_batch_m(job.h, e, slot_m[e])
                 with torch.cuda.stream(job.main):
                     sweep.fill_(1.0)
                 if i >= 0:
@@ -509,7 +521,7 @@ def measure(torch, a, cid, headline, oracle_leg):
                 enter(e)
                 if mask is not None:
                     job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
-                B.es_accumulate_batch(job.h, e, all_buckets, slot_ptrs[e])
+                B.es_accumulate_batch_m(job.h, e, slot_m[e])
             leave()
             finish()
 
@@ -523,9 +535,28 @@ def measure(torch, a, cid, headline, oracle_leg):
                 if e in last_of_worker:
                     B.es_accumulate_in_place(job.h, e, src[e].data_ptr())
                 else:
-                    B.es_accumulate_batch(job.h, e, all_buckets, src_ptrs[e])
+                    B.es_accumulate_batch_m(job.h, e, marshalled[e])
             leave()
             finish()
+
+        # several ESTs' gradients resident at once (one EST of each worker that shares the GPU, or
+        # buffers not reused yet): 16 ESTs staged per launch by es_accumulate_many
+        flat_ptrs = [src[e].data_ptr() for e in range(N)]
+
+        def step_many():
+            for e in sched:
+                enter(e)
+                if mask is not None:
+                    job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
+            leave()
+            B.es_accumulate_many(job.h, sched, [flat_ptrs[e] for e in sched])
+            finish()
+
+        ms_many = timed_wall(step_many)
+        res["staged_16_per_launch_step"] = {
+            "note": "all ESTs' gradients resident until the end of the step and staged 16 per launch "
+                    "(es_accumulate_many)", "ms_per_step": round(ms_many, 4),
+            "value": round(total / (ms_many * 1e-3) / 1e9, 2), "unit": "GB/s"}
 
         ms_ip = timed_wall(step_in_place_last)
         res["in_place_last_step"] = {
@@ -684,7 +715,9 @@ def main():
                    "n_buckets": head["n_buckets"],
                    "mode": "fused reduce+sgd" if fused else "reduce, then sgd",
                    "streams": a.streams, "slots": "pinned host memory" if a.host_slots else "HBM",
-                   "staging": "per bucket" if a.per_bucket else "batched per EST", **head["options"]},
+                   "staging": ("per bucket" if a.per_bucket else "batched per EST, context switch a launch of its own"
+                               if a.separate_calls else "one launch per EST boundary (stage + save + restore)"),
+                   **head["options"]},
         "step_bytes": head["step_bytes"],
         "roofline": {"bound": "hbm" if not a.host_slots else "host link (not an HBM figure)",
                      "kernel": red["kernel"], "achieved": red["achieved"], "peak": HBM_PEAK_GBPS,
@@ -703,7 +736,7 @@ def main():
         "est_switch": switch,
         "ceilings": ceil,
     }
-    for k in ("sgd", "reduce_hbm_only", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
+    for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
               "checkpoint", "cold_step"):
         if k in head:
             out[k] = head[k]

@@ -203,6 +203,38 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
                         const float* const* d_grad_buckets);
 
 /*
+ * es_accumulate of ALL buckets of several ESTs at once, each from one flat gradient
+ * vector (paper section 3.2's per-EST gradient copy, for the case that several ESTs'
+ * gradients are resident at the same time: one EST of each worker that shares the
+ * device, or buffers the framework has not reused yet).  Up to 16 ESTs travel in one
+ * kernel launch, more in several.
+ *   ests          HOST array of n_ests distinct virtual ranks
+ *   d_flat_grads  HOST array of n_ests DEVICE pointers: n_params floats each in flat
+ *                 parameter order, 4-byte aligned; a pointer that equals the EST's slot
+ *                 (es_grad_slot(est, 0)) only marks that EST as present
+ * Same rules as es_accumulate per (est, bucket); validation covers the whole call
+ * before anything is enqueued or marked.
+ */
+int es_accumulate_many(es_handle* h, uint32_t n_ests, const uint32_t* ests,
+                       const float* const* d_flat_grads);
+
+/*
+ * One EST boundary in ONE kernel launch (paper section 3.2: at a mini-batch boundary the
+ * outgoing EST's context is saved, its gradients are copied aside, and the next EST's
+ * context is restored): es_accumulate_batch(est_out, ...) fused with
+ * es_ctx_switch(est_out, est_in), or with es_ctx_save(est_out) if est_in is ES_NO_EST
+ * (the last EST a worker runs in a global step).  Same results as the separate calls.
+ * Runs on the stage stream, after the work already enqueued on main and on ctx; if est_in
+ * is given, work enqueued on main afterwards waits for it (it needs the restored state), so
+ * with separate streams this call does not overlap the copy with the next EST's compute:
+ * callers who want that overlap use the separate calls.  est_out and est_in must be on the
+ * same worker, whose live state must be bound if the layout has state segments.
+ */
+#define ES_NO_EST 0xFFFFFFFFu
+int es_est_boundary(es_handle* h, uint32_t est_out, uint32_t est_in, uint32_t n,
+                    const uint32_t* buckets, const float* const* d_grad_buckets);
+
+/*
  * Take ALL buckets of one EST in place, without a staging copy: the next reduce
  * reads this EST's gradients straight from d_flat_grad.  This is the paper's
  * treatment of the last EST a worker runs in a global step: it does not copy its

@@ -80,6 +80,10 @@ _SIGS = {
     "es_accumulate": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, _VP]),
     "es_accumulate_batch": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32,
                                            ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(_VP)]),
+    "es_accumulate_many": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.POINTER(ctypes.c_uint32),
+                                          ctypes.POINTER(_VP)]),
+    "es_est_boundary": (ctypes.c_int, [_VP, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32,
+                                       ctypes.POINTER(ctypes.c_uint32), ctypes.POINTER(_VP)]),
     "es_accumulate_in_place": (ctypes.c_int, [_VP, ctypes.c_uint32, _VP]),
     "es_grad_slot": (_VP, [_VP, ctypes.c_uint32, ctypes.c_uint32]),
     "es_stage_fence": (ctypes.c_int, [_VP]),
@@ -192,6 +196,40 @@ def es_accumulate_batch(h, est, buckets: Sequence[int], d_grads: Sequence[int]) 
     b = (ctypes.c_uint32 * max(1, n))(*buckets)
     g = (_VP * max(1, n))(*d_grads)
     return lib().es_accumulate_batch(h, est, n, b, g)
+
+
+ES_NO_EST = 0xFFFFFFFF
+
+
+class Marshalled:
+    """Bucket indices and device pointers of one batch as C arrays, built once and handed to
+    es_accumulate_batch / es_est_boundary again every global step (marshalling only)."""
+
+    def __init__(self, buckets: Sequence[int], d_grads: Sequence[int]):
+        self.n = len(buckets)
+        self.b = (ctypes.c_uint32 * max(1, self.n))(*buckets)
+        self.g = (_VP * max(1, self.n))(*d_grads)
+
+
+def es_accumulate_batch_m(h, est, m: Marshalled) -> int:
+    return lib().es_accumulate_batch(h, est, m.n, m.b, m.g)
+
+
+def es_accumulate_many(h, ests: Sequence[int], d_flat_grads: Sequence[int]) -> int:
+    n = len(ests)
+    e = (ctypes.c_uint32 * max(1, n))(*ests)
+    g = (_VP * max(1, n))(*d_flat_grads)
+    return lib().es_accumulate_many(h, n, e, g)
+
+
+def es_est_boundary(h, est_out, est_in, buckets: Sequence[int], d_grads: Sequence[int]) -> int:
+    """``est_in`` None or ES_NO_EST: save est_out only."""
+    m = Marshalled(buckets, d_grads)
+    return lib().es_est_boundary(h, est_out, ES_NO_EST if est_in is None else est_in, m.n, m.b, m.g)
+
+
+def es_est_boundary_m(h, est_out, est_in, m: Marshalled) -> int:
+    return lib().es_est_boundary(h, est_out, ES_NO_EST if est_in is None else est_in, m.n, m.b, m.g)
 
 
 def es_accumulate_in_place(h, est, d_flat_grad): return lib().es_accumulate_in_place(h, est, d_flat_grad)

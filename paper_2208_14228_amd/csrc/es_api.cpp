@@ -619,13 +619,14 @@ int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_gr
     return ES_OK;
 }
 
-int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
-                        const float* const* d_grad_buckets)
+namespace {
+
+// A batch of buckets of one EST, checked as a whole: a failing call enqueues nothing and marks nothing.
+int validate_batch(const es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
+                   const float* const* srcs)
 {
-    if (!h || est >= h->N || (n && (!buckets || !d_grad_buckets))) return ES_EINVAL;
-    DeviceGuard guard__(h);
+    if (est >= h->N || (n && (!buckets || !srcs))) return ES_EINVAL;
     const size_t nb = h->buckets.size();
-    // validate everything first: a failing call must enqueue nothing and mark nothing
     uint64_t blocks_bound = 0;               // workgroups of the whole batch: a bound on every launch's grid
     for (uint32_t k = 0; k < n; ++k) {
         const uint32_t b = buckets[k];
@@ -633,64 +634,164 @@ int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* 
         const uint64_t len = h->buckets[b].len_elems;
         blocks_bound += ((len >> 2) + kCopyBlock - 1) / kCopyBlock + 1;
         if (blocks_bound > 0x7fffffffull) return ES_EINVAL;
-        const float* src = d_grad_buckets[k];
+        const float* src = srcs[k];
         if (len && (!src || (((uintptr_t)src) & 3))) return ES_EINVAL;
         for (uint32_t j = 0; j < k; ++j)
             if (buckets[j] == b) return ES_ESTATE;
         if (h->accumulated[(size_t)est * nb + b]) return ES_ESTATE;
-        const float* dst = es_grad_slot(h, est, b);
-        if (len && src != dst) {
-            const uintptr_t a = (uintptr_t)src, d = (uintptr_t)dst, sz = len * sizeof(float);
-            if (a < d + sz && d < a + sz) return ES_EINVAL;
-        }
+        const float* dst = slot_base(h, est) + h->buckets[b].offset_elems;
+        if (len && src != dst && overlap(src, dst, len * sizeof(float))) return ES_EINVAL;
     }
-    bool ordered = false;
-    CopyRuns runs;
-    runs.n_runs = 0;
-    runs.first_block[0] = 0;
-    auto flush = [&]() -> int {
-        if (runs.n_runs == 0) return ES_OK;
-        for (uint32_t k = runs.n_runs + 1; k <= (uint32_t)kMaxRuns; ++k) runs.first_block[k] = 0xFFFFFFFFu;
-        ES_HIP(h, launch_copy_runs(h->s_stage, runs));
-        runs.n_runs = 0;
-        runs.first_block[0] = 0;
-        return ES_OK;
-    };
+    return ES_OK;
+}
+
+// Staging copies as launches of at most kMaxRuns contiguous runs each.
+struct RunBuilder {
+    std::vector<CopyRuns> launches;
+    void add(float* dst, const float* src, uint64_t len)
+    {
+        if (launches.empty()) open();
+        CopyRuns* r = &launches.back();
+        // extend the previous run when source and destination both continue it
+        if (r->n_runs && r->src[r->n_runs - 1] + r->n[r->n_runs - 1] == src &&
+            r->dst[r->n_runs - 1] + r->n[r->n_runs - 1] == dst &&
+            r->first_block[r->n_runs - 1] + blocks_of(r->n[r->n_runs - 1] + len) <= 0x7fffffffull) {
+            r->n[r->n_runs - 1] += len;
+        } else {
+            if (r->n_runs == (uint32_t)kMaxRuns || r->first_block[r->n_runs] + blocks_of(len) > 0x7fffffffull) {
+                open();
+                r = &launches.back();
+            }
+            r->dst[r->n_runs] = dst;
+            r->src[r->n_runs] = src;
+            r->n[r->n_runs] = len;
+            ++r->n_runs;
+        }
+        r->first_block[r->n_runs] = r->first_block[r->n_runs - 1] + (uint32_t)blocks_of(r->n[r->n_runs - 1]);
+    }
+    static uint64_t blocks_of(uint64_t len)
+    {
+        const uint64_t blocks = ((len >> 2) + kCopyBlock - 1) / kCopyBlock;
+        return blocks ? blocks : 1;
+    }
+    void open()
+    {
+        launches.emplace_back();
+        CopyRuns& r = launches.back();
+        r.n_runs = 0;
+        for (int k = 0; k <= kMaxRuns; ++k) r.first_block[k] = 0xFFFFFFFFu;   // "no run starts here"
+        r.first_block[0] = 0;
+    }
+};
+
+void collect_runs(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets, const float* const* srcs,
+                  RunBuilder& rb)
+{
     for (uint32_t k = 0; k < n; ++k) {
-        const uint32_t b = buckets[k];
-        const uint64_t len = h->buckets[b].len_elems;
-        const float* src = d_grad_buckets[k];
-        float* dst = es_grad_slot(h, est, b);
-        if (len && src != dst) {
-            if (!ordered) {
-                int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
-                if (rc != ES_OK) return rc;
-                ordered = true;
-            }
-            // extend the previous run when source and destination both continue it
-            uint32_t& nr = runs.n_runs;
-            if (nr && runs.src[nr - 1] + runs.n[nr - 1] == src && runs.dst[nr - 1] + runs.n[nr - 1] == dst) {
-                runs.n[nr - 1] += len;
-            } else {
-                if (nr == (uint32_t)kMaxRuns) {
-                    int rc = flush();
-                    if (rc != ES_OK) return rc;
-                }
-                runs.dst[nr] = dst;
-                runs.src[nr] = src;
-                runs.n[nr] = len;
-                ++nr;
-            }
-            const uint64_t vec = runs.n[nr - 1] >> 2;
-            uint64_t blocks = (vec + kCopyBlock - 1) / kCopyBlock;
-            if (blocks == 0) blocks = 1;
-            runs.first_block[nr] = runs.first_block[nr - 1] + (uint32_t)blocks;
-            h->stage_pending = true;
-        }
-        h->accumulated[(size_t)est * nb + b] = 1;
-        h->n_accumulated++;
+        const uint64_t len = h->buckets[buckets[k]].len_elems;
+        float* dst = slot_base(h, est) + h->buckets[buckets[k]].offset_elems;
+        if (len && srcs[k] != dst) rb.add(dst, srcs[k], len);
     }
-    return flush();
+}
+
+void mark_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets)
+{
+    const size_t nb = h->buckets.size();
+    for (uint32_t k = 0; k < n; ++k) h->accumulated[(size_t)est * nb + buckets[k]] = 1;
+    h->n_accumulated += n;
+}
+
+}  // namespace
+
+int es_accumulate_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets,
+                        const float* const* d_grad_buckets)
+try {
+    if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
+    int rc = validate_batch(h, est, n, buckets, d_grad_buckets);
+    if (rc != ES_OK) return rc;
+    RunBuilder rb;
+    collect_runs(h, est, n, buckets, d_grad_buckets, rb);
+    if (!rb.launches.empty()) {
+        if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;
+        for (const CopyRuns& r : rb.launches) ES_HIP(h, launch_copy_runs(h->s_stage, r));
+        h->stage_pending = true;
+    }
+    mark_batch(h, est, n, buckets);
+    return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
+}
+
+int es_accumulate_many(es_handle* h, uint32_t n_ests, const uint32_t* ests, const float* const* d_flat_grads)
+try {
+    if (!h || (n_ests && (!ests || !d_flat_grads))) return ES_EINVAL;
+    DeviceGuard guard__(h);
+    const size_t nb = h->buckets.size();
+    const uint64_t vec_bytes = h->P * sizeof(float);
+    if (RunBuilder::blocks_of(h->P) > 0x7fffffffull) return ES_EINVAL;
+    for (uint32_t k = 0; k < n_ests; ++k) {
+        const uint32_t e = ests[k];
+        if (e >= h->N) return ES_EINVAL;
+        const float* src = d_flat_grads[k];
+        if (h->P && (!src || (((uintptr_t)src) & 3))) return ES_EINVAL;
+        for (uint32_t j = 0; j < k; ++j)
+            if (ests[j] == e) return ES_ESTATE;
+        for (size_t b = 0; b < nb; ++b)
+            if (h->accumulated[(size_t)e * nb + b]) return ES_ESTATE;
+        if (h->P && src != slot_base(h, e) && overlap(src, slot_base(h, e), vec_bytes)) return ES_EINVAL;
+    }
+    RunBuilder rb;
+    for (uint32_t k = 0; k < n_ests; ++k)
+        if (h->P && d_flat_grads[k] != slot_base(h, ests[k])) rb.add(slot_base(h, ests[k]), d_flat_grads[k], h->P);
+    if (!rb.launches.empty()) {
+        int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
+        if (rc != ES_OK) return rc;
+        for (const CopyRuns& r : rb.launches) ES_HIP(h, launch_copy_runs(h->s_stage, r));
+        h->stage_pending = true;
+    }
+    for (uint32_t k = 0; k < n_ests; ++k)
+        for (size_t b = 0; b < nb; ++b) h->accumulated[(size_t)ests[k] * nb + b] = 1;
+    h->n_accumulated += (uint64_t)n_ests * nb;
+    return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
+}
+
+int es_est_boundary(es_handle* h, uint32_t est_out, uint32_t est_in, uint32_t n, const uint32_t* buckets,
+                    const float* const* d_grad_buckets)
+try {
+    if (!h || est_out >= h->N) return ES_EINVAL;
+    const bool has_in = est_in != ES_NO_EST;
+    if (has_in && (est_in >= h->N || est_in == est_out)) return ES_EINVAL;
+    DeviceGuard guard__(h);
+    if (has_in && h->worker_of[est_out] != h->worker_of[est_in]) return ES_EINVAL;
+    const Worker& w = h->workers[h->worker_of[est_out]];
+    if (!h->seg_bytes.empty() && !w.bound) return ES_ESTATE;
+    int rc = validate_batch(h, est_out, n, buckets, d_grad_buckets);
+    if (rc != ES_OK) return rc;
+    RunBuilder rb;
+    collect_runs(h, est_out, n, buckets, d_grad_buckets, rb);
+    const uint32_t n_pieces = h->seg_bytes.empty() ? 0 : w.n_pieces;
+    if (n_pieces || !rb.launches.empty()) {
+        // after the outgoing EST's compute on main and after earlier context traffic on the ctx stream
+        if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;
+        if (h->s_ctx != h->s_main && (rc = order_after(h, h->s_stage, h->s_ctx, h->ev_ctx)) != ES_OK) return rc;
+        if (rb.launches.empty()) rb.open();
+        ES_HIP(h, launch_est_boundary(h->s_stage, rb.launches[0], w.d_pieces, n_pieces, ctx_base(h, est_out),
+                                      has_in ? ctx_base(h, est_in) : nullptr, has_in ? kSwitch : kSave));
+        for (size_t k = 1; k < rb.launches.size(); ++k) ES_HIP(h, launch_copy_runs(h->s_stage, rb.launches[k]));
+        h->stage_pending = true;
+    }
+    mark_batch(h, est_out, n, buckets);
+    // the incoming EST's compute on main must see its restored state
+    if (has_in && n_pieces) {
+        if ((rc = order_after(h, h->s_main, h->s_stage, h->ev_stage)) != ES_OK) return rc;
+        h->stage_pending = false;
+    }
+    return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
 }
 
 int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad)

@@ -34,6 +34,7 @@ constexpr uint32_t kBlock = 256;
 #define ES_REDUCE_BLOCK 256
 #endif
 constexpr uint32_t kReduceBlock = ES_REDUCE_BLOCK;   // lanes per workgroup of the ring-ordered reduce
+constexpr int kBigEpilogue = 16;                     // vectors per lane per pass of a big tile's update epilogue
 constexpr uint32_t kCopyBlock = ES_COPY_BLOCK;   // lanes per workgroup of the batched staging copy
 
 // Entries of the rank -> gradient-base table that are redirected for one reduce
@@ -90,6 +91,12 @@ enum CtxDir { kSave = 0, kRestore = 1, kSwitch = 2 };
 // kSwitch:  slot_a <- live, then live <- slot_b (per byte, same lane)
 hipError_t launch_ctx(hipStream_t s, const Piece* pieces, uint32_t n_pieces,
                       uint8_t* slot_a, const uint8_t* slot_b, CtxDir dir);
+
+// One launch for an EST boundary: the small-state pieces (kSave or kSwitch) and the staging
+// copy of the outgoing EST's runs.  runs.n_runs may be 0, n_pieces may be 0.  The unused
+// prefix-sum entries of `runs` must hold 0xFFFFFFFF as for launch_copy_runs.
+hipError_t launch_est_boundary(hipStream_t s, const CopyRuns& runs, const Piece* pieces, uint32_t n_pieces,
+                               uint8_t* slot_a, const uint8_t* slot_b, CtxDir dir);
 
 // generic byte copy used when contexts move between arenas
 hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, uint64_t n);

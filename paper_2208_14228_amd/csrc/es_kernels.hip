@@ -244,12 +244,6 @@ __device__ __forceinline__ void fold_batch_lin(const float* const ES_CONST_AS* s
     }
 }
 
-template <int U, int NB, int NT, bool SGD>
-__device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots, uint32_t N,
-                                           uint64_t off, uint32_t len, uint32_t rank0,
-                                           float* __restrict__ avg, float* __restrict__ p,
-                                           float* __restrict__ v, float lr, float mu);
-
 template <int UB, int NBB, int NT, bool SGD>
 __global__ __launch_bounds__(kReduceBlock) void k_ring_reduce_big(const Tile* tiles_g, uint32_t n_big,
                                                             const float* const* slots_g, uint32_t N,
@@ -288,19 +282,23 @@ __global__ __launch_bounds__(kReduceBlock) void k_ring_reduce_big(const Tile* ti
         if (r0 >= N) r0 -= N;
         fold_batch_lin<UB, 1, NT, false>(slots, N, r0, e0, acc);
     }
-    // epilogue four vectors at a time so p and v never need UB registers each
+    // Epilogue kBigEpilogue vectors at a time, in the registers the rank loads have left free:
+    // 2 * 16 loads of parameters and momentum in flight, then their stores (measured against
+    // groups of 4: +3 % at N = 16, +2 % at N = 64; parameter and momentum accesses alternating
+    // as here beat all of one, then all of the other).
+    constexpr int EG = (kBigEpilogue < UB) ? kBigEpilogue : UB;
 #pragma unroll
-    for (int u0 = 0; u0 < UB; u0 += 4) {
-        f4 pp[4], vv[4];
+    for (int u0 = 0; u0 < UB; u0 += EG) {
+        f4 pp[EG], vv[EG];
         if constexpr (SGD) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
+            for (int q = 0; q < EG; ++q) {
                 pp[q] = ld4_pv<(NT & 2) != 0>(p + e0 + 256 * (u0 + q));
                 vv[q] = ld4_pv<(NT & 2) != 0>(v + e0 + 256 * (u0 + q));
             }
         }
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < EG; ++q) {
             const uint64_t e = e0 + 256 * (u0 + q);
             const f4 a = acc[u0 + q] / fN;
             if (avg) st4(avg + e, a);
@@ -747,10 +745,10 @@ hipError_t launch_copy_bytes(hipStream_t s, uint8_t* dst, const uint8_t* src, ui
 // In kSwitch every lane reads its live bytes, then overwrites them with the
 // incoming EST's bytes: outgoing and incoming state never meet across lanes.
 // ---------------------------------------------------------------------------
-template <typename T>
+template <typename T, uint32_t BS = kBlock>
 __device__ __forceinline__ void ctx_move(T* live, T* sa, const T* sb, uint32_t n, int dir)
 {
-    for (uint32_t i = threadIdx.x; i < n; i += kBlock) {
+    for (uint32_t i = threadIdx.x; i < n; i += BS) {
         if (dir == kSave) {
             sa[i] = live[i];
         } else if (dir == kRestore) {
@@ -764,22 +762,60 @@ __device__ __forceinline__ void ctx_move(T* live, T* sa, const T* sb, uint32_t n
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_ctx(const Piece* pieces_g, uint8_t* slot_a,
-                                                const uint8_t* slot_b, int dir)
+template <uint32_t BS>
+__device__ __forceinline__ void ctx_piece(const Piece ES_CONST_AS* pieces, uint32_t k, uint8_t* slot_a,
+                                          const uint8_t* slot_b, int dir)
 {
-    const Piece ES_CONST_AS* pieces = (const Piece ES_CONST_AS*)pieces_g;
-    uint8_t* live = (uint8_t*)pieces[blockIdx.x].live;
-    const uint64_t so = pieces[blockIdx.x].slot_off;
-    const uint32_t nb = pieces[blockIdx.x].nbytes;
-    const uint32_t w = pieces[blockIdx.x].width;
+    uint8_t* live = (uint8_t*)pieces[k].live;
+    const uint64_t so = pieces[k].slot_off;
+    const uint32_t nb = pieces[k].nbytes;
+    const uint32_t w = pieces[k].width;
     uint8_t* sa = slot_a + so;
     const uint8_t* sb = slot_b ? slot_b + so : nullptr;
     if (w == 16)
-        ctx_move<u4>((u4*)live, (u4*)sa, (const u4*)sb, nb >> 4, dir);
+        ctx_move<u4, BS>((u4*)live, (u4*)sa, (const u4*)sb, nb >> 4, dir);
     else if (w == 4)
-        ctx_move<uint32_t>((uint32_t*)live, (uint32_t*)sa, (const uint32_t*)sb, nb >> 2, dir);
+        ctx_move<uint32_t, BS>((uint32_t*)live, (uint32_t*)sa, (const uint32_t*)sb, nb >> 2, dir);
     else
-        ctx_move<uint8_t>(live, sa, sb, nb, dir);
+        ctx_move<uint8_t, BS>(live, sa, sb, nb, dir);
+}
+
+__global__ __launch_bounds__(kBlock) void k_ctx(const Piece* pieces_g, uint8_t* slot_a,
+                                                const uint8_t* slot_b, int dir)
+{
+    ctx_piece<kBlock>((const Piece ES_CONST_AS*)pieces_g, blockIdx.x, slot_a, slot_b, dir);
+}
+
+// An EST boundary in one launch (paper section 3.2: at a mini-batch boundary the outgoing EST's
+// context is saved, its gradients are copied aside, and the incoming EST's context is restored):
+// the first n_pieces workgroups move small-state pieces (save, or save + restore per byte in one
+// lane), all others are the staging copy of the outgoing EST's gradient runs.  The two parts touch
+// disjoint memory, so no ordering between them is needed inside the launch.
+__global__ __launch_bounds__(kCopyBlock) void k_est_boundary(const CopyRuns runs, const Piece* pieces_g,
+                                                             uint32_t n_pieces, uint8_t* slot_a,
+                                                             const uint8_t* slot_b, int dir)
+{
+    if (blockIdx.x < n_pieces) {
+        ctx_piece<kCopyBlock>((const Piece ES_CONST_AS*)pieces_g, blockIdx.x, slot_a, slot_b, dir);
+        return;
+    }
+    const uint32_t blk = blockIdx.x - n_pieces;
+    uint32_t r = 0;
+    if (runs.n_runs > 1) {
+#pragma unroll
+        for (int k = 1; k < kMaxRuns; ++k) r += blk >= runs.first_block[k] ? 1u : 0u;
+    }
+    copy_span(runs.dst[r], runs.src[r], runs.n[r], blk - runs.first_block[r], threadIdx.x, kCopyBlock);
+}
+
+hipError_t launch_est_boundary(hipStream_t s, const CopyRuns& runs, const Piece* pieces, uint32_t n_pieces,
+                               uint8_t* slot_a, const uint8_t* slot_b, CtxDir dir)
+{
+    const uint32_t copy_blocks = runs.n_runs ? runs.first_block[runs.n_runs] : 0;
+    if (n_pieces + copy_blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_est_boundary, dim3(n_pieces + copy_blocks), dim3(kCopyBlock), 0, s, runs, pieces,
+                       n_pieces, slot_a, slot_b, (int)dir);
+    return hipGetLastError();
 }
 
 hipError_t launch_ctx(hipStream_t s, const Piece* pieces, uint32_t n_pieces, uint8_t* slot_a,

@@ -63,7 +63,22 @@ int main(void)
         HIP(hipMemcpy(dg, hg, sizeof(float) * N * P, hipMemcpyHostToDevice));
 
         /* library */
-        for (uint32_t e = 0; e < N; ++e) {
+        /* the ways of handing gradients over: several ESTs in one launch, one EST boundary in one
+           launch, one bucket at a time, and in place */
+        uint32_t first = 0;
+        if (step == 0) {
+            const uint32_t two[2] = { 0, 1 };
+            const float *flat[2] = { dg, dg + P };
+            ES(es_accumulate_many(h, 2, two, flat));
+            first = 2;
+        } else {
+            uint32_t idx[NB];
+            const float *src[NB];
+            for (uint32_t b = 0; b < NB; ++b) { idx[b] = b; src[b] = dg + buckets[b].offset_elems; }
+            ES(es_est_boundary(h, 0, ES_NO_EST, NB, idx, src));
+            first = 1;
+        }
+        for (uint32_t e = first; e < N; ++e) {
             if (step == 1 && e == N - 1) { ES(es_accumulate_in_place(h, e, dg + (uint64_t)e * P)); continue; }
             for (uint32_t b = 0; b < NB; ++b)
                 ES(es_accumulate(h, e, b, dg + (uint64_t)e * P + buckets[b].offset_elems));

@@ -17,6 +17,7 @@ hipError_t launch_copy_f32(hipStream_t, float*, const float*, uint64_t) { return
 hipError_t launch_copy_runs(hipStream_t, const CopyRuns&) { return hipSuccess; }
 hipError_t launch_patch_slots(hipStream_t, const float**, const InPlace&) { return hipSuccess; }
 hipError_t launch_ctx(hipStream_t, const Piece*, uint32_t, uint8_t*, const uint8_t*, CtxDir) { return hipSuccess; }
+hipError_t launch_est_boundary(hipStream_t, const CopyRuns&, const Piece*, uint32_t, uint8_t*, const uint8_t*, CtxDir) { return hipSuccess; }
 hipError_t launch_copy_bytes(hipStream_t, uint8_t*, const uint8_t*, uint64_t) { return hipSuccess; }
 hipError_t launch_sq_norm(hipStream_t, const float*, uint64_t, float*, float*) { return hipSuccess; }
 hipError_t launch_sq_norm_static(hipStream_t, const float*, uint64_t, float*) { return hipSuccess; }

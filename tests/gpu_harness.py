@@ -93,18 +93,30 @@ def init_contexts(sc: S.Scenario, job: ESTJob) -> None:
 def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=False,
               sync_each_est=False, masks: Optional[Dict] = None, mask_check=None,
               steps: Optional[Sequence[int]] = None, batched=False, store_avg=True,
-              src_shift=0) -> None:
+              src_shift=0, boundary=False, many=0) -> None:
     """``batched``: one flat gradient vector per EST handed over with es_accumulate_batch (what
     bench.py times) instead of one tensor and one es_accumulate per bucket; ``src_shift`` moves
     that vector 0-3 elements off its 16-byte boundary (sources then sit differently from the
-    slots, or equally for buckets at a matching odd offset)."""
+    slots, or equally for buckets at a matching odd offset).  ``boundary``: every EST boundary is
+    one es_est_boundary call (stage the outgoing EST, save it, restore the next EST of the worker).
+    ``many`` > 0: gradients are kept until that many ESTs have run (or the step ends) and then
+    staged together by es_accumulate_many."""
+    if boundary or many:
+        batched = True
     mask = torch.empty(sc.mask_n, dtype=torch.uint8, device=DEV) if sc.mask_n else None
     sched = g.schedule()
     for t in (range(sc.steps) if steps is None else steps):
         keep = []
+        pending = []
         for idx, e in enumerate(sched):
             prev = sched[idx - 1] if idx else None
-            if (use_switch and prev is not None
+            nxt = sched[idx + 1] if idx + 1 < len(sched) else None
+            if nxt is not None and g.worker_of_est[nxt] != g.worker_of_est[e]:
+                nxt = None
+            if boundary:
+                if prev is None or g.worker_of_est[prev] != g.worker_of_est[e]:
+                    job.ctx_restore(e)            # first EST of its worker; later ones arrive by a boundary
+            elif (use_switch and prev is not None
                     and g.worker_of_est[prev] == g.worker_of_est[e]):
                 job.ctx_switch(prev, e)
             else:
@@ -125,20 +137,32 @@ def run_steps(sc: S.Scenario, job: ESTJob, g: Grouping, fused=False, use_switch=
                     for b, (off, ln) in enumerate(sc.layout.buckets):
                         synth.gradient(sc.layout, b, sc.seed, t, e, DEV, out=flat[off:off + ln])
                     keep.append(flat)
-                    job.accumulate_batch(e, list(range(sc.layout.n_buckets)),
-                                         [flat[off:off + ln] for off, ln in sc.layout.buckets])
+                    if boundary:
+                        B.check(B.es_est_boundary(job.h, e, nxt, list(range(sc.layout.n_buckets)),
+                                                  [flat.data_ptr() + 4 * off for off, _ in sc.layout.buckets]),
+                                "es_est_boundary", job.h)
+                    elif many:
+                        pending.append((e, flat))
+                        if len(pending) == many or idx + 1 == len(sched):
+                            B.check(B.es_accumulate_many(job.h, [x for x, _ in pending],
+                                                         [f.data_ptr() for _, f in pending]),
+                                    "es_accumulate_many", job.h)
+                            pending.clear()
+                    else:
+                        job.accumulate_batch(e, list(range(sc.layout.n_buckets)),
+                                             [flat[off:off + ln] for off, ln in sc.layout.buckets])
                 else:
                     for b in range(sc.layout.n_buckets):
                         gr = S.grad(sc, t, e, b, DEV)
                         keep.append(gr)
                         job.accumulate(e, b, gr)
-            if not use_switch:
+            if not use_switch and not boundary:
                 job.ctx_save(e)
-            if sync_each_est:
+            if sync_each_est and not pending:
                 job.sync()
                 torch.cuda.synchronize()
                 keep.clear()
-        if use_switch:
+        if use_switch and not boundary:
             job.ctx_save(sched[-1])
         if fused:
             job.reduce_sgd_step(sc.lr, sc.momentum, store_avg=store_avg)
@@ -166,7 +190,7 @@ def collect(sc: S.Scenario, job: ESTJob, masks: Dict) -> S.Result:
 
 
 def run_gpu(sc: S.Scenario, g: Grouping, fused=False, use_switch=False, use_streams=True,
-            options=None, live_alloc=None, batched=False, src_shift=0) -> S.Result:
+            options=None, live_alloc=None, batched=False, src_shift=0, boundary=False, many=0) -> S.Result:
     print(f"[gpu-run] N={sc.n_logical} P={sc.layout.n_params} A={sc.chunk_align} seed={sc.seed:#x} "
           f"grouping={g.name} fused={fused} switch={use_switch} streams={use_streams} opts={options}",
           flush=True)
@@ -174,7 +198,8 @@ def run_gpu(sc: S.Scenario, g: Grouping, fused=False, use_switch=False, use_stre
     try:
         init_contexts(sc, job)
         masks: Dict = {}
-        run_steps(sc, job, g, fused, use_switch, masks=masks, batched=batched, src_shift=src_shift)
+        run_steps(sc, job, g, fused, use_switch, masks=masks, batched=batched, src_shift=src_shift,
+                  boundary=boundary, many=many)
         return collect(sc, job, masks)
     finally:
         job.close()

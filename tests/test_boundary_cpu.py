@@ -59,6 +59,8 @@ def test_null_handle_is_rejected_everywhere():
     assert B.es_accumulate(0, 0, 0, 0) == B.ES_EINVAL
     assert B.es_accumulate_batch(0, 0, [0], [0]) == B.ES_EINVAL
     assert B.es_accumulate_in_place(0, 0, 0) == B.ES_EINVAL
+    assert B.es_accumulate_many(0, [0], [0]) == B.ES_EINVAL
+    assert B.es_est_boundary(0, 0, None, [0], [0]) == B.ES_EINVAL
     assert B.es_grad_slot(0, 0, 0) == 0
     assert B.es_ring_order_reduce(0, 0) == B.ES_EINVAL
     assert B.es_sgd_step(0, 0, 0, 0, 0.1, 0.9) == B.ES_EINVAL

@@ -50,12 +50,13 @@ def test_full_replay(cid):
 
 
 def bench_launch_configuration(sc, g, want_p, want_v):
-    """Exactly what bench.py times: one in-order stream, one flat gradient vector per EST
-    staged by es_accumulate_batch, fused switch, fused reduce+update without storing the average."""
+    """Exactly what bench.py times: one in-order stream, one flat gradient vector per EST, every EST
+    boundary one es_est_boundary launch (stage + save + restore of the next EST), fused reduce+update
+    without storing the average."""
     job = G.make_job(sc, g, use_streams="one")
     try:
         G.init_contexts(sc, job)
-        G.run_steps(sc, job, g, fused=True, use_switch=True, batched=True, store_avg=False,
+        G.run_steps(sc, job, g, fused=True, boundary=True, store_avg=False,
                     sync_each_est=sc.layout.n_params * sc.n_logical > (1 << 31))
         if isinstance(want_p, np.ndarray):
             assert np.array_equal(bits(job.p.cpu().numpy()), bits(want_p)), "bench configuration: parameters"

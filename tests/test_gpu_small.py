@@ -462,7 +462,7 @@ def test_in_place_state_rules():
         assert B.es_accumulate_in_place(h, 0, g.data_ptr()) == B.ES_ESTATE            # a bucket already present
         for e in range(1, 9):
             assert B.es_accumulate_in_place(h, e, g.data_ptr()) == B.ES_OK
-        assert B.es_accumulate_in_place(h, 9, g.data_ptr()) == B.ES_ESTATE            # more than 8 per step
+        assert B.es_accumulate_in_place(h, 8, g.data_ptr()) == B.ES_ESTATE            # already taken in place
         assert B.es_accumulate(h, 1, 0, g.data_ptr()) == B.ES_ESTATE                  # already counted
         assert B.es_accumulate_batch(h, 9, [0, 1], [g.data_ptr(), g.data_ptr() + 128]) == B.ES_OK
         assert B.es_accumulate(h, 0, 0, g.data_ptr()) == B.ES_OK
@@ -658,3 +658,114 @@ def test_staging_from_sources_off_a_16_byte_boundary():
             assert np.array_equal(bits(job.avg.cpu().numpy()), bits(ref.avg)), f"per bucket shift {shift}"
     finally:
         job.close()
+
+
+def test_est_boundary_in_one_launch_matches_the_separate_calls():
+    """es_est_boundary = staging of the outgoing EST + save + restore of the next EST of its worker in
+    one kernel launch: same bits as the reference for every grouping, on one stream and on three."""
+    N = 8
+    sc = ragged_scenario(N, 4, 91, steps=3, mask_n=517, bn_channels=(64, 3, 128, 2048))
+    ref = S.run_ddp_reference(sc)
+    for g in (configs.contiguous([8]), configs.contiguous([3, 5]), configs.round_robin([2, 6]),
+              configs.contiguous([1] * 8, "1x8")):
+        for streams in ("one", True):
+            got = G.run_gpu(sc, g, fused=True, boundary=True, use_streams=streams)
+            S.assert_same(got, ref, f"boundary {g.name} streams={streams}")
+    # a layout without small state: the boundary is the staging copy alone
+    sc2 = ragged_scenario(5, 1, 92, steps=2)
+    S.assert_same(G.run_gpu(sc2, configs.contiguous([2, 3]), boundary=True), S.run_ddp_reference(sc2),
+                  "boundary without state")
+
+
+def test_est_boundary_state_rules():
+    job = ESTJob(4, 64, [(0, 32), (32, 32)], 4, [16, 64], [0, 0, 1, 1], [0, 1, 0, 1])
+    h = job.h
+    try:
+        g = torch.zeros(64, device=G.DEV)
+        ptrs = [g.data_ptr(), g.data_ptr() + 128]
+        assert B.es_est_boundary(h, 0, 0, [0, 1], ptrs) == B.ES_EINVAL            # switch to itself
+        assert B.es_est_boundary(h, 0, 2, [0, 1], ptrs) == B.ES_EINVAL            # other worker
+        assert B.es_est_boundary(h, 4, None, [0, 1], ptrs) == B.ES_EINVAL
+        assert B.es_est_boundary(h, 0, 7, [0, 1], ptrs) == B.ES_EINVAL
+        assert B.es_est_boundary(h, 0, 1, [0, 0], ptrs) == B.ES_ESTATE            # duplicate bucket
+        assert B.es_est_boundary(h, 0, 1, [0, 5], ptrs) == B.ES_EINVAL
+        assert B.es_est_boundary(h, 0, 1, [0, 1], ptrs) == B.ES_OK
+        assert B.es_est_boundary(h, 0, 1, [0], ptrs[:1]) == B.ES_ESTATE           # already staged
+        assert B.es_est_boundary(h, 1, None, [0, 1], ptrs) == B.ES_OK
+        assert B.es_est_boundary(h, 2, 3, [], []) == B.ES_OK                      # context only
+        assert B.es_sync(h) == B.ES_OK
+    finally:
+        job.close()
+    # live state not bound: refused
+    st, h2 = B.es_init(2, 64, [(0, 64)], 4, [16])
+    assert st == B.ES_OK
+    try:
+        g = torch.zeros(64, device=G.DEV)
+        assert B.es_est_boundary(h2, 0, 1, [0], [g.data_ptr()]) == B.ES_ESTATE
+    finally:
+        B.es_destroy(h2)
+
+
+def test_accumulate_many_matches_per_est_staging():
+    """Several ESTs' flat gradients staged by one launch (more ESTs than one launch carries, sources
+    off a 16-byte boundary, one EST produced in its slot), against the reference."""
+    N = 20
+    sc = ragged_scenario(N, 4, 93, steps=2, bn_channels=(5, 16))
+    ref = S.run_ddp_reference(sc)
+    for g, many, shift in ((configs.contiguous([20]), 20, 0), (configs.contiguous([7, 13]), 3, 1),
+                           (configs.contiguous([1] * 20, "1x20"), 17, 2)):
+        got = G.run_gpu(sc, g, fused=True, many=many, src_shift=shift)
+        S.assert_same(got, ref, f"many={many} {g.name}")
+
+
+def test_accumulate_many_state_rules():
+    job = ESTJob(3, 64, [(0, 32), (32, 32)], 4)
+    h = job.h
+    try:
+        g = [torch.full((64,), float(k + 1), device=G.DEV) for k in range(3)]
+        p = [t.data_ptr() for t in g]
+        torch.cuda.synchronize()
+        assert B.es_accumulate_many(h, [0, 0], [p[0], p[1]]) == B.ES_ESTATE       # duplicate EST
+        assert B.es_accumulate_many(h, [0, 3], [p[0], p[1]]) == B.ES_EINVAL
+        assert B.es_accumulate_many(h, [0, 1], [p[0], 0]) == B.ES_EINVAL          # null source
+        assert B.es_accumulate_many(h, [0, 1], [p[0], p[1] + 2]) == B.ES_EINVAL   # not 4-byte aligned
+        assert B.es_accumulate(h, 2, 1, p[2] + 128) == B.ES_OK
+        assert B.es_accumulate_many(h, [1, 2], [p[1], p[2]]) == B.ES_ESTATE       # EST 2 partly present
+        # EST 1 writes its gradient straight into its slot: only marked
+        slot1 = B.es_grad_slot(h, 1, 0)
+        torch.cuda.synchronize()
+        assert B.es_accumulate_many(h, [0], [p[0]]) == B.ES_OK
+        assert B.es_accumulate(h, 2, 0, p[2]) == B.ES_OK
+        assert B.es_accumulate_many(h, [1], [slot1]) == B.ES_OK
+        assert B.es_accumulate_many(h, [], []) == B.ES_OK
+        assert B.es_ring_order_reduce(h, job.avg.data_ptr()) == B.ES_OK
+        assert B.es_sync(h) == B.ES_OK
+    finally:
+        job.close()
+
+
+def test_every_est_taken_in_place():
+    """No staging at all: the reduce reads all N gradient vectors where the caller left them
+    (more ESTs than one table-patch launch carries), two steps, small and big tiles."""
+    for N, opts in ((5, None), (40, {"reduce_big_unroll": 8})):
+        sc = ragged_scenario(N, 4, 300 + N, steps=2)
+        ref = S.run_ddp_reference(sc)
+        job = G.make_job(sc, configs.contiguous([N]), options=opts)
+        try:
+            G.init_contexts(sc, job)
+            for t in range(sc.steps):
+                flats = []
+                with job.stream_ctx():
+                    for e in range(N):
+                        flat = torch.empty(sc.layout.n_params, dtype=torch.float32, device=G.DEV)
+                        for b, (off, ln) in enumerate(sc.layout.buckets):
+                            synth.gradient(sc.layout, b, sc.seed, t, e, G.DEV, out=flat[off:off + ln])
+                        flats.append(flat)
+                for e in range(N):
+                    job.accumulate_in_place(e, flats[e])
+                job.reduce_sgd_step(sc.lr, sc.momentum, store_avg=True)
+                job.sync()
+                torch.cuda.synchronize()
+            S.assert_same(G.collect(sc, job, {}), ref, f"all {N} in place")
+        finally:
+            job.close()
