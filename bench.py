@@ -503,7 +503,7 @@ def measure(torch, a, cid, headline, oracle_leg):
                     "at this size, streaming_pv = option nontemporal_pv=1", **cold}
         del sweep
 
-    if headline and not a.no_extras:
+    if not a.no_extras:
         def timed_wall(fn):
             for _ in range(warmup):
                 fn()
@@ -578,6 +578,7 @@ def measure(torch, a, cid, headline, oracle_leg):
                                  "ms_per_step": round(ms_zc, 4),
                                  "value": round((total - bytes_stage) / (ms_zc * 1e-3) / 1e9, 2), "unit": "GB/s"}
 
+    if headline and not a.no_extras:
         # fixed-tree global norm of a vector of the job's size (one read of 4P bytes)
         out2 = torch.zeros(2, device=dev)
         for _ in range(3):
@@ -742,7 +743,8 @@ def main():
             out[k] = head[k]
     if not a.no_configs:
         keep = ("config", "workload", "ms_per_step", "step_GBps", "step_frac", "step_bytes", "reduce", "staging",
-                "reduce_hbm_only", "cold_step", "context_bytes_per_est", "mask_bytes_per_est", "zero_ulp",
+                "reduce_hbm_only", "cold_step", "staged_16_per_launch_step", "in_place_last_step", "graph_step",
+                "zero_copy_step", "context_bytes_per_est", "mask_bytes_per_est", "zero_ulp",
                 "cpu_baseline", "cpu_baseline_all_cores")
         allc = dict(short)
         allc[a.config] = head

@@ -102,7 +102,9 @@ typedef struct es_bucket_layout {
 } es_bucket_layout;
 
 /*
- * Create a job with n_logical ESTs (1 .. 65535) on the current HIP device.
+ * Create a job of n_logical EasyScaleThreads (paper section 3.2: the logical workers
+ * whose number, not the number of GPUs, fixes the training procedure; 1 .. 65535) on
+ * the current HIP device, with the recorded bucket mapping of section 3.3 (D1).
  * Starts with one simulated worker that holds all ESTs (slot = rank), all
  * streams = the null stream, and no live state bound.
  * Allocates n_logical gradient slots of n_params floats and n_logical small
@@ -157,9 +159,15 @@ int es_set_grouping(es_handle* h, uint32_t n_workers,
  */
 int es_bind_live_state(es_handle* h, uint32_t worker, void* const* live_ptrs);
 
-/* slot[est] -> live tensors of est's worker.  One batched copy kernel on the ctx stream. */
+/*
+ * Context switching, paper section 3.2: when an EST is scheduled its context is
+ * loaded into the worker's live state; section 3.3 names the small states that
+ * belong to it (RNG state, BatchNorm statistics).
+ * slot[est] -> live tensors of est's worker.  One batched copy kernel on the ctx stream.
+ */
 int es_ctx_restore(es_handle* h, uint32_t est);
 /*
+ * Paper section 3.2: at the end of an EST's mini-batch its context is saved.
  * live tensors of est's worker -> slot[est].  One batched copy kernel on the ctx stream.
  * Work enqueued on main afterwards is NOT made to wait for the save (so the
  * save of a step's last EST overlaps with the reduce): the live tensors must
@@ -191,7 +199,8 @@ int es_ctx_switch(es_handle* h, uint32_t est_out, uint32_t est_in);
 int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_grad_bucket);
 
 /*
- * es_accumulate for several buckets of one EST at once (same rules per bucket).
+ * es_accumulate (paper section 3.2, section 5.1.3: the per-EST gradient copy) for several
+ * buckets of one EST at once, same rules per bucket.
  *   buckets         HOST array of n distinct bucket indices
  *   d_grad_buckets  HOST array of n DEVICE pointers, one source per bucket
  * Up to 16 runs are copied by one kernel launch; sources that continue each other
@@ -250,7 +259,12 @@ int es_est_boundary(es_handle* h, uint32_t est_out, uint32_t est_in, uint32_t n,
  */
 int es_accumulate_in_place(es_handle* h, uint32_t est, const float* d_flat_grad);
 
-/* DEVICE address of est's slot for `bucket` (NULL on bad arguments).  Changes at es_set_grouping. */
+/*
+ * Where EST `est` keeps gradient bucket `bucket` (paper section 3.2: the gradients are the
+ * part of an EST's context that is kept per EST until the global step ends).  A backward
+ * pass that writes there needs no copy (see es_accumulate).  DEVICE address, NULL on bad
+ * arguments; changes at es_set_grouping.
+ */
 float* es_grad_slot(es_handle* h, uint32_t est, uint32_t bucket);
 
 /* Makes work enqueued on main after this call wait for all staging copies enqueued so far. */

@@ -52,3 +52,13 @@ def test_norm_special_values_and_alignment():
     assert gpu_norm(x)[0] == 100_003.0
     assert gpu_norm(x, shift=1) == B.ES_EINVAL           # 4-byte aligned only: rejected
     assert gpu_norm(x, shift=4)[0] == 100_003.0          # 16-byte aligned view
+
+
+def test_hand_derived_tree_witness_on_gpu():
+    """The two order witnesses of tests/golden/tree_witness.txt: the kernel's tree has to be the
+    specified one, not merely agree with the oracle."""
+    from test_oracle_tree import golden_witness, witness_inputs
+    gold = golden_witness()
+    for name, x in witness_inputs().items():
+        got = gpu_norm(x)
+        assert int(got[0].view(np.uint32)) == gold[name][2], (name, got)

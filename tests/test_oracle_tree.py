@@ -74,3 +74,93 @@ def test_error_bound_and_order_dependence():
     for v in (x[:20000] * x[:20000]):
         naive = np.float32(naive + v)
     assert np.float32(oracle.tree_sumsq(x[:20000])).view(np.uint32) != naive.view(np.uint32)
+
+
+# ---- hand-derived order witnesses (tests/golden/tree_witness.txt) ----------------------
+def witness_inputs():
+    """The two input vectors the golden file describes, built from its own wording."""
+    def elem(lane, q, c):
+        return 4 * (256 * q + lane) + c
+    a = np.zeros(4096, dtype=np.float32)
+    a[elem(0, 1, 0)] = 4096
+    for pos in ((0, 0, 0), (0, 0, 1), (0, 1, 1), (128, 0, 0), (128, 0, 1), (128, 0, 2), (64, 0, 0),
+                (192, 0, 0), (192, 2, 3), (1, 0, 0), (2, 3, 3)):
+        a[elem(*pos)] = 1
+    b = np.zeros(515 * 4096, dtype=np.float32)
+    b[0] = 4096
+    for blk in (255, 256, 257, 512):
+        b[4096 * blk] = 1
+    return {"A": a, "B": b}
+
+
+def golden_witness():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tree_witness.txt")
+    rows = {}
+    for line in open(path):
+        if line.strip() and not line.startswith("#"):
+            name, n, val, bits_hex = line.split()
+            rows[name] = (int(n), np.float32(float(val)), int(bits_hex, 16))
+    return rows
+
+
+def test_hand_derived_tree_witness():
+    inputs, gold = witness_inputs(), golden_witness()
+    assert set(gold) == {"A", "B"}
+    for name, x in inputs.items():
+        n, val, want_bits = gold[name]
+        assert x.size == n and int(val.view(np.uint32)) == want_bits
+        got = np.float32(oracle.tree_sumsq(x))
+        assert int(got.view(np.uint32)) == want_bits, (name, float(got))
+
+
+def test_witness_tells_other_summation_orders_apart():
+    """What the golden file says about other conventions, checked: each gives another value on the
+    witness, so a tree that is wrong in one of these ways cannot pass it."""
+    f = np.float32
+    a = witness_inputs()["A"]
+    sq = a * a
+    base = f(2.0 ** 24)
+
+    def halving(lane):
+        s = lane.size // 2
+        while s >= 1:
+            lane = lane[:s] + lane[s:2 * s]
+            s //= 2
+        return lane[0]
+
+    running = f(0)
+    for v in sq[np.nonzero(sq)[0]]:
+        running = f(running + v)
+    pairs = sq.copy()
+    while pairs.size > 1:
+        pairs = pairs[0::2] + pairs[1::2]
+    lanes = np.zeros(256, dtype=f)
+    for q in range(4):
+        for c in range(4):
+            lanes = lanes + sq.reshape(4, 256, 4)[q, :, c]
+    adjacent = lanes.copy()
+    while adjacent.size > 1:
+        adjacent = adjacent[0::2] + adjacent[1::2]
+    c_outer = np.zeros(256, dtype=f)
+    for c in range(4):
+        for q in range(4):
+            c_outer = c_outer + sq.reshape(4, 256, 4)[q, :, c]
+    strided = np.zeros(256, dtype=f)
+    for k in range(16):
+        strided = strided + sq.reshape(16, 256)[k]
+    assert halving(lanes) - base == 12                     # the specified tree, written a second time
+    assert running - base == 8 and pairs[0] - base == 10 and adjacent[0] - base == 8
+    assert halving(c_outer) - base == 8 and halving(strided) - base == 8
+
+    b = witness_inputs()["B"]
+    part = (b[::4096] * b[::4096]).astype(f)
+    rows = np.zeros(3 * 256, dtype=f)
+    rows[:part.size] = part
+    rows = rows.reshape(3, 256)
+    assert halving((rows[0] + rows[1]) + rows[2]) - base == 2        # partials t, t+256, t+512 in that order
+    assert halving((rows[2] + rows[1]) + rows[0]) - base == 4        # descending instead
+    run = f(0)
+    for v in part:
+        run = f(run + v)
+    assert run - base == 0
