@@ -5,8 +5,9 @@ Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
 Python binding) never does, and this package imports nothing of the product.
 
   es_oracle.c       message-passing ring all-reduce among N simulated ranks,
-                    /N, SGD-momentum, Philox4x32-10 dropout mask, fixed-tree sum of
-                    squares (plain C, fp32)
+                    /N, SGD-momentum (also with the gradient clipped by its global
+                    norm), Philox4x32-10 dropout mask, fixed-tree sum of squares and
+                    BatchNorm batch statistics along the same tree (plain C, fp32)
   fold_def.py       the closed form of the same reduction (per-chunk rotated
                     left fold) in numpy: cross-check of the simulator and
                     evaluator of sampled outputs at sizes the simulator cannot hold
@@ -23,7 +24,11 @@ independent big-integer implementation, vs. the Philox engine that ships in
 PyTorch's headers, and round-function invertibility; dropout keep rate and
 stream splitting; the fixed-tree sum of squares vs. a numpy twin built from
 reshapes, exact integer cases, single-element cases and the pairwise-summation
-error bound.  No function here is "parity unpinned".
+error bound, and two hand-derived order witnesses (tests/golden/tree_witness.txt);
+the clip coefficient vs. exact rational rounding and the unclipped case vs. the plain
+update; BatchNorm statistics vs. the witnesses, exact dyadic cases, a numpy twin, the
+float64 mean/variance within the summation error bound, and layout permutations.
+No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -90,6 +95,13 @@ def lib() -> ctypes.CDLL:
         L.eso_dropout_mask.restype = None
         L.eso_tree_sumsq.argtypes = [f32p, ctypes.c_uint64]
         L.eso_tree_sumsq.restype = ctypes.c_float
+        L.eso_clip_coef.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_float]
+        L.eso_clip_coef.restype = ctypes.c_float
+        L.eso_sgd_momentum_scaled.argtypes = [f32p, f32p, f32p, ctypes.c_uint64, ctypes.c_float,
+                                              ctypes.c_float, ctypes.c_float]
+        L.eso_sgd_momentum_scaled.restype = None
+        L.eso_bn_batch_stats.argtypes = [f32p, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, f32p, f32p]
+        L.eso_bn_batch_stats.restype = None
         _lib = L
     return _lib
 
@@ -169,3 +181,25 @@ def tree_sumsq(x: np.ndarray) -> np.float32:
     """Sum of squares of a flat fp32 vector along the fixed tree (see es_oracle.c)."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     return np.float32(lib().eso_tree_sumsq(_f32(x) if x.size else None, x.size))
+
+
+def clip_coef(norm, max_norm, eps) -> np.float32:
+    """min(1, max_norm / (norm + eps)), every operation rounded to fp32."""
+    return np.float32(lib().eso_clip_coef(np.float32(norm), np.float32(max_norm), np.float32(eps)))
+
+
+def sgd_momentum_scaled(p: np.ndarray, v: np.ndarray, g: np.ndarray, lr: float, mu: float, coef) -> None:
+    """In place: g' = coef*g ; v <- mu*v + g' ; p <- p - lr*v (fp32, every operation rounded)."""
+    assert p.shape == v.shape == g.shape
+    lib().eso_sgd_momentum_scaled(_f32(p), _f32(v), _f32(g), p.size, lr, mu, np.float32(coef))
+
+
+def bn_batch_stats(x: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Per-channel mean and biased variance of x[B, C, HW] along the fixed tree (see es_oracle.c)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    B, C, HW = x.shape
+    mean = np.empty(C, dtype=np.float32)
+    var = np.empty(C, dtype=np.float32)
+    if C:
+        lib().eso_bn_batch_stats(_f32(x) if x.size else None, B, C, HW, _f32(mean), _f32(var))
+    return mean, var

@@ -273,3 +273,96 @@ float eso_tree_sumsq(const float *x, uint64_t n)
     free(part);
     return total;
 }
+
+/* ------------------------------------------------------------------ *
+ * Gradient clipping by the global norm, folded into the update.  The paper
+ * does not discuss clipping; this is the usual convention of training
+ * frameworks, stated in full: the whole averaged gradient is multiplied by
+ *     coef = min(1, max_norm / (norm + eps))
+ * where norm is the square root of the fixed-tree sum of squares above; the
+ * sum, the division and the product are each rounded to fp32.  With coef = 1
+ * the product g * 1 is g itself, so an unclipped step equals eso_sgd_momentum.
+ * ------------------------------------------------------------------ */
+float eso_clip_coef(float norm, float max_norm, float eps)
+{
+    float d = norm + eps;
+    float c = max_norm / d;
+    return c < 1.0f ? c : 1.0f;
+}
+
+void eso_sgd_momentum_scaled(float *p, float *v, const float *g, uint64_t n, float lr, float mu, float coef)
+{
+    #pragma omp parallel for schedule(static)
+    for (uint64_t i = 0; i < n; ++i) {
+        float gs = coef * g[i];
+        float mv = mu * v[i];
+        float vn = mv + gs;
+        float step = lr * vn;
+        v[i] = vn;
+        p[i] = p[i] - step;
+    }
+}
+
+/* ------------------------------------------------------------------ *
+ * BatchNorm batch statistics along the fixed tree (the paper's level D2,
+ * section 3.3, asks of "reduce" that its result not depend on the GPU; BatchNorm
+ * is the operator of section 3.3 whose statistics every EST tracks).
+ * x is laid out [B][C][HW] (images, channels, spatial positions).  For channel
+ * ch the M = B*HW values in the order (image, position) form a vector
+ * y[m] = x[(m / HW) * C + ch][m % HW].  With T(f) the tree of eso_tree_sumsq
+ * applied to the terms f(y[m]) instead of squares (blocks of 4096 terms, 256
+ * lanes x (q outer, c inner), stride-halving, second stage over the block
+ * partials; terms beyond M count as +0):
+ *     mean[ch] = T(y) / (float)M
+ *     var[ch]  = T((y - mean[ch])^2) / (float)M        (the biased variance)
+ * every subtraction, square, add and division rounded to fp32.
+ * ------------------------------------------------------------------ */
+static float eso_tree_channel(const float *x, uint64_t C, uint64_t HW, uint64_t M, uint64_t ch,
+                              int squared_deviation, float center)
+{
+    uint64_t nblk = (M + 4095) / 4096;
+    float *part = (float *)malloc((nblk ? nblk : 1) * sizeof(float));
+    float v[256];
+    for (uint64_t b = 0; b < nblk; ++b) {
+        for (int t = 0; t < 256; ++t) {
+            float s = 0.0f;
+            for (int q = 0; q < 4; ++q)
+                for (int c = 0; c < 4; ++c) {
+                    uint64_t m = b * 4096 + 4 * (uint64_t)(256 * q + t) + c;
+                    float term = 0.0f;
+                    if (m < M) {
+                        float y = x[((m / HW) * C + ch) * HW + m % HW];
+                        if (squared_deviation) {
+                            float d = y - center;
+                            term = d * d;
+                        } else {
+                            term = y;
+                        }
+                    }
+                    s = s + term;
+                }
+            v[t] = s;
+        }
+        part[b] = eso_tree256(v);
+    }
+    for (int t = 0; t < 256; ++t) {
+        float s = 0.0f;
+        for (uint64_t k = t; k < nblk; k += 256)
+            s = s + part[k];
+        v[t] = s;
+    }
+    float total = eso_tree256(v);
+    free(part);
+    return total;
+}
+
+void eso_bn_batch_stats(const float *x, uint64_t B, uint64_t C, uint64_t HW, float *mean, float *var)
+{
+    uint64_t M = B * HW;
+    float fm = (float)M;
+    for (uint64_t ch = 0; ch < C; ++ch) {
+        float mu = eso_tree_channel(x, C, HW, M, ch, 0, 0.0f) / fm;
+        mean[ch] = mu;
+        var[ch] = eso_tree_channel(x, C, HW, M, ch, 1, mu) / fm;
+    }
+}
