@@ -595,6 +595,46 @@ def measure(torch, a, cid, headline, oracle_leg):
                                "achieved": round(4 * P / (norm_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                                "frac": round(4 * P / (norm_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
 
+        # the update with the gradient clipped by that norm (coefficient formed on the device)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(-2, steps):
+            if i == 0:
+                c0.record(job.main)
+            B.es_clip_sgd_step(job.h, job.p.data_ptr(), job.v.data_ptr(), job.avg.data_ptr(), out2.data_ptr(),
+                               1.0, 1e-6, cfg.lr, cfg.momentum)
+        c1.record(job.main)
+        job.sync(); torch.cuda.synchronize()
+        clip_ms = c0.elapsed_time(c1) / steps
+        res["clip_sgd_step"] = {"note": "k_sgd_clip: update with the averaged gradient clipped by its fixed-tree "
+                                        "norm, 5*4P bytes", "avg_ms": round(clip_ms, 4),
+                                "achieved": round(20 * P / (clip_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                                "frac": round(20 * P / (clip_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+
+        # BatchNorm batch statistics along the fixed tree, on the activation shape of ResNet-50's first
+        # BatchNorm layer at batch 32 (32 x 64 x 112 x 112 fp32 = 103 MB; two passes over it)
+        bn_shape = (32, 64, 112 * 112)
+        xbn = torch.randn(bn_shape, device=dev)
+        nws = B.es_bn_workspace_floats(*bn_shape)
+        ws = torch.empty(nws, device=dev)
+        mv = torch.empty(2, 64, device=dev)
+        torch.cuda.synchronize()
+        b0, b1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(-2, steps):
+            if i == 0:
+                b0.record(job.main)
+            B.es_bn_batch_stats(xbn.data_ptr(), *bn_shape, mv[0].data_ptr(), mv[1].data_ptr(), ws.data_ptr(), nws,
+                                job.main.cuda_stream)
+        b1.record(job.main)
+        job.sync(); torch.cuda.synchronize()
+        bn_ms = b0.elapsed_time(b1) / steps
+        bn_bytes = 2 * 4 * xbn.numel()
+        res["bn_batch_stats"] = {"note": "k_bn_partials + k_bn_final twice (mean, then variance) on 32x64x112x112 "
+                                         "fp32; bytes = two reads of the activations (the second can come from "
+                                         "the Infinity Cache: 103 MB)", "avg_ms": round(bn_ms, 4),
+                                 "achieved": round(bn_bytes / (bn_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                                 "frac": round(bn_bytes / (bn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        del xbn, ws, mv
+
         # on-demand checkpoint (all EST contexts by virtual rank + one copy of p and v) to a pinned
         # host blob and back: host-link traffic, timed on the wall clock (the calls are synchronous)
         ck_n = B.es_checkpoint_bytes(job.h)
@@ -738,7 +778,7 @@ def main():
         "ceilings": ceil,
     }
     for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
-              "checkpoint", "cold_step"):
+              "clip_sgd_step", "bn_batch_stats", "checkpoint", "cold_step"):
         if k in head:
             out[k] = head[k]
     if not a.no_configs:

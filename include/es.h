@@ -333,6 +333,42 @@ int es_reduce_sgd_step(es_handle* h, float* d_param, float* d_momentum,
 int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2);
 
 /*
+ * es_sgd_step with the averaged gradient clipped by its global norm first (the usual
+ * convention of training frameworks; the paper does not discuss clipping): with norm =
+ * d_norm2[1] as es_grad_sq_norm left it in device memory (no host round trip),
+ *     coef = min(1, max_norm / (norm + eps)) ;  g' = coef * g ;  v <- mu*v + g' ;  p <- p - lr*v
+ * every operation rounded to fp32 on its own.  Because the norm comes from the fixed tree the
+ * clipped step is as independent of the launch as everything else here; with coef = 1 the
+ * result is that of es_sgd_step.  Buffers as for es_sgd_step; d_norm2 DEVICE, 2 floats;
+ * max_norm >= 0, eps >= 0 (ES_EINVAL otherwise).  Runs on main.  The usual sequence is
+ * es_ring_order_reduce(avg), es_grad_sq_norm(avg, norm2), es_clip_sgd_step(.., avg, norm2, ..).
+ */
+int es_clip_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_avg_grad,
+                     const float* d_norm2, float max_norm, float eps, float lr, float mu);
+
+/*
+ * BatchNorm batch statistics along the same fixed tree (paper section 3.3: BatchNorm is the
+ * operator whose statistics belong to the EST context; level D2 asks of reductions that their
+ * result not depend on the GPU).  Needs no handle.
+ *   d_x     DEVICE, n_images x n_channels x n_positions floats (NCHW with H*W = n_positions),
+ *           4-byte aligned
+ *   d_mean, d_var  DEVICE, n_channels floats each
+ * For every channel the M = n_images * n_positions values in the order (image, position) are
+ * the terms of the tree described at es_grad_sq_norm (terms instead of squares, terms beyond M
+ * count as +0):  mean = T(y) / (float)M ;  var = T((y - mean)^2) / (float)M  (biased variance),
+ * every subtraction, square, add and division rounded to fp32.  No atomics; the first stage
+ * uses wave shuffles, the second an LDS stage.
+ *   d_workspace      DEVICE scratch of at least es_bn_workspace_floats(..) floats, 4-byte aligned
+ *   stream           HOST value of a hipStream_t on the current device (NULL = null stream)
+ * Limits: M < 2^31, n_channels <= 65535, n_images and n_positions > 0 (ES_EINVAL otherwise;
+ * es_bn_workspace_floats returns 0 for sizes it rejects or that need no scratch).
+ */
+uint64_t es_bn_workspace_floats(uint64_t n_images, uint64_t n_channels, uint64_t n_positions);
+int es_bn_batch_stats(const float* d_x, uint64_t n_images, uint64_t n_channels, uint64_t n_positions,
+                      float* d_mean, float* d_var, float* d_workspace, uint64_t workspace_floats,
+                      void* stream);
+
+/*
  * es_grad_sq_norm for callers that cannot allocate device memory: code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Needs no
  * handle and calls no hipMalloc / hipFree or any allocating routine: the block

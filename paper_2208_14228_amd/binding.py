@@ -94,6 +94,11 @@ _SIGS = {
     "es_reduce_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float]),
     "es_grad_sq_norm": (ctypes.c_int, [_VP, _VP, _VP]),
     "es_grad_sq_norm_static": (ctypes.c_int, [_VP, ctypes.c_uint64, _VP, _VP]),
+    "es_clip_sgd_step": (ctypes.c_int, [_VP, _VP, _VP, _VP, _VP, ctypes.c_float, ctypes.c_float,
+                                        ctypes.c_float, ctypes.c_float]),
+    "es_bn_workspace_floats": (ctypes.c_uint64, [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64]),
+    "es_bn_batch_stats": (ctypes.c_int, [_VP, ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64, _VP, _VP,
+                                         _VP, ctypes.c_uint64, _VP]),
     "es_checkpoint_bytes": (ctypes.c_uint64, [_VP]),
     "es_checkpoint_export": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP, ctypes.c_uint64]),
     "es_checkpoint_import": (ctypes.c_int, [_VP, _VP, ctypes.c_uint64, _VP, _VP,
@@ -254,6 +259,20 @@ def es_reduce_sgd_step(h, d_param, d_momentum, d_avg, lr, mu):
 
 def es_grad_sq_norm(h, d_vec, d_out2): return lib().es_grad_sq_norm(h, d_vec, d_out2)
 def es_grad_sq_norm_static(d_vec, n, d_out2, stream=0): return lib().es_grad_sq_norm_static(d_vec, n, d_out2, stream)
+def es_clip_sgd_step(h, d_param, d_momentum, d_avg, d_norm2, max_norm, eps, lr, mu):
+    return lib().es_clip_sgd_step(h, d_param, d_momentum, d_avg, d_norm2, max_norm, eps, lr, mu)
+
+
+def es_bn_workspace_floats(n_images, n_channels, n_positions):
+    return lib().es_bn_workspace_floats(n_images, n_channels, n_positions)
+
+
+def es_bn_batch_stats(d_x, n_images, n_channels, n_positions, d_mean, d_var, d_workspace, workspace_floats,
+                      stream=0):
+    return lib().es_bn_batch_stats(d_x, n_images, n_channels, n_positions, d_mean, d_var, d_workspace,
+                                   workspace_floats, stream)
+
+
 def es_checkpoint_bytes(h): return lib().es_checkpoint_bytes(h)
 
 

@@ -914,6 +914,43 @@ int es_grad_sq_norm(es_handle* h, const float* d_vec, float* d_out2)
     return ES_OK;
 }
 
+int es_clip_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_avg_grad,
+                     const float* d_norm2, float max_norm, float eps, float lr, float mu)
+{
+    if (!h) return ES_EINVAL;
+    DeviceGuard guard__(h);
+    if (!d_norm2 || (((uintptr_t)d_norm2) & 3) || !(max_norm >= 0.0f) || !(eps >= 0.0f)) return ES_EINVAL;
+    if (h->P && (!d_param || !d_momentum || !d_avg_grad)) return ES_EINVAL;
+    if (!aligned16(d_param) || !aligned16(d_momentum) || !aligned16(d_avg_grad)) return ES_EINVAL;
+    const uint64_t vec_bytes = h->P * sizeof(float);
+    if (overlap(d_param, d_momentum, vec_bytes) || overlap(d_param, d_avg_grad, vec_bytes) ||
+        overlap(d_momentum, d_avg_grad, vec_bytes))
+        return ES_EINVAL;
+    ES_HIP(h, launch_sgd_clip(h->s_main, d_param, d_momentum, d_avg_grad, h->P, d_norm2, max_norm, eps, lr, mu));
+    return ES_OK;
+}
+
+uint64_t es_bn_workspace_floats(uint64_t n_images, uint64_t n_channels, uint64_t n_positions)
+{
+    if (n_images == 0 || n_positions == 0) return 0;
+    if (n_images > (1ull << 31) / n_positions) return 0;
+    return n_channels * ((n_images * n_positions + 4095) / 4096);
+}
+
+int es_bn_batch_stats(const float* d_x, uint64_t n_images, uint64_t n_channels, uint64_t n_positions,
+                      float* d_mean, float* d_var, float* d_workspace, uint64_t workspace_floats, void* stream)
+{
+    if (n_images == 0 || n_positions == 0 || n_channels > 65535) return ES_EINVAL;
+    if (n_positions >= (1ull << 31) || n_images > ((1ull << 31) - 1) / n_positions) return ES_EINVAL;
+    if (n_channels == 0) return ES_OK;
+    if (!d_x || !d_mean || !d_var || !d_workspace) return ES_EINVAL;
+    if ((((uintptr_t)d_x) | ((uintptr_t)d_mean) | ((uintptr_t)d_var) | ((uintptr_t)d_workspace)) & 3) return ES_EINVAL;
+    if (workspace_floats < es_bn_workspace_floats(n_images, n_channels, n_positions)) return ES_EINVAL;
+    return launch_bn_batch_stats((hipStream_t)stream, d_x, (uint32_t)n_images, (uint32_t)n_channels,
+                                 (uint32_t)n_positions, d_mean, d_var, d_workspace) == hipSuccess
+               ? ES_OK : ES_EHIP;
+}
+
 int es_grad_sq_norm_static(const float* d_vec, uint64_t n, float* d_out2, void* stream)
 {
     if (!d_out2 || (((uintptr_t)d_out2) & 3)) return ES_EINVAL;

@@ -111,6 +111,15 @@ hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part
 constexpr uint64_t kStaticPartials = 1ull << 18;
 hipError_t launch_sq_norm_static(hipStream_t s, const float* x, uint64_t n, float* out);
 
+// v <- mu*v + coef*g ; p <- p - lr*v with coef = min(1, max_norm / (norm2[1] + eps)) formed on the device
+hipError_t launch_sgd_clip(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
+                           const float* norm2, float max_norm, float eps, float lr, float mu);
+
+// Per-channel mean and biased variance of x[B][C][HW] along the fixed tree; B * HW < 2^31,
+// C <= 65535; part: scratch of C * ceil(B * HW / 4096) floats
+hipError_t launch_bn_batch_stats(hipStream_t s, const float* x, uint32_t B, uint32_t C, uint32_t HW,
+                                 float* mean, float* var, float* part);
+
 hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, uint64_t n,
                                uint64_t threshold);
 

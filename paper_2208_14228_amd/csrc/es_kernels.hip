@@ -485,6 +485,67 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
     return hipGetLastError();
 }
 
+// The same update with the gradient clipped by its global norm first: every lane forms
+//     coef = min(1, max_norm / (norm + eps))
+// from the norm es_grad_sq_norm left in device memory (no host round trip) and scales its
+// gradient elements by it; coef * g is rounded on its own before it enters the momentum.
+__global__ __launch_bounds__(kBlock) void k_sgd_clip(float* __restrict__ p, float* __restrict__ v,
+                                                     const float* __restrict__ g, uint64_t n,
+                                                     const float* __restrict__ norm2, float max_norm,
+                                                     float eps, float lr, float mu)
+{
+    const float d = norm2[1] + eps;
+    const float q = max_norm / d;
+    const float coef = q < 1.0f ? q : 1.0f;
+    const uint64_t nvec = n >> 2;
+    const uint64_t base = (uint64_t)blockIdx.x * (kBlock * kSgdU) + threadIdx.x;
+    f4 pp[kSgdU], vv[kSgdU], gg[kSgdU];
+#pragma unroll
+    for (int u = 0; u < kSgdU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) {
+            gg[u] = ld4<true>(g + 4 * i);
+            pp[u] = ld4<false>(p + 4 * i);
+            vv[u] = ld4<false>(v + 4 * i);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kSgdU; ++u) {
+        const uint64_t i = base + (uint64_t)u * kBlock;
+        if (i < nvec) {
+            const f4 gs = coef * gg[u];
+            const f4 mv = mu * vv[u];
+            const f4 vn = mv + gs;
+            const f4 st = lr * vn;
+            st4(v + 4 * i, vn);
+            st4(p + 4 * i, pp[u] - st);
+        }
+    }
+    if (blockIdx.x == 0) {
+        const uint64_t e = 4 * nvec + threadIdx.x;
+        if (e < n) {
+            const float gs = coef * g[e];
+            const float mv = mu * v[e];
+            const float vn = mv + gs;
+            const float st = lr * vn;
+            v[e] = vn;
+            p[e] = p[e] - st;
+        }
+    }
+}
+
+hipError_t launch_sgd_clip(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
+                           const float* norm2, float max_norm, float eps, float lr, float mu)
+{
+    if (n == 0) return hipSuccess;
+    const uint64_t nvec = n >> 2;
+    uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(k_sgd_clip, dim3((uint32_t)blocks), dim3(kBlock), 0, s, p, v, g, n, norm2, max_norm,
+                       eps, lr, mu);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Fixed-tree sum of squares of a flat vector (global gradient norm).  In the
 // spirit of the paper's level D2 (section 3.3: reductions must not depend on
@@ -902,6 +963,116 @@ hipError_t launch_dropout_mask(hipStream_t s, uint64_t* state, uint8_t* mask, ui
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_philox_advance, dim3(1), dim3(64), 0, s, state, (n + 3) / 4);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// BatchNorm batch statistics along the fixed tree (the paper's level D2, section 3.3: a
+// reduce whose result does not depend on the GPU; BatchNorm is the operator whose statistics
+// every EST tracks).  x is [B][C][HW].  For channel ch the M = B*HW values in the order
+// (image, position) form a vector y; its terms f(y[m]) are summed along the tree of the norm
+// (blocks of 4096 terms; lane t adds terms 4*(256*q + t) + c, q outer, c inner, from +0;
+// stride halving over 256 lanes; block partials combined the same way, lane t first adding
+// partials t, t+256, ...).  mean = T(y) / M, var = T((y - mean)^2) / M.
+//
+// First stage: one WAVE per block of one channel; hardware lane h plays tree lanes h, h+64,
+// h+128, h+192 (strides 128 and 64 are adds between its own registers, 32..1 wave shuffles).
+// Second stage: one workgroup per channel with an LDS stage.  No atomics.
+// ---------------------------------------------------------------------------
+template <bool SQDEV>
+__global__ __launch_bounds__(kBlock) void k_bn_partials(const float* __restrict__ x, uint32_t C, uint32_t HW,
+                                                        uint32_t M, uint32_t nblk,
+                                                        const float* __restrict__ mean,
+                                                        float* __restrict__ part)
+{
+    const uint32_t h = threadIdx.x & 63;
+    const uint32_t blk = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const uint32_t ch = blockIdx.y;
+    if (blk >= nblk) return;                            // whole wave leaves together
+    const float center = SQDEV ? mean[ch] : 0.0f;
+    const uint32_t base = blk * 4096;
+    f4 t[4][4];                                         // [tree lane h + 64 j][q]: four consecutive terms
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t m0 = base + 4u * (256 * q + 64 * j + h);
+            const uint32_t img = m0 / HW, pos = m0 - img * HW;
+            f4 e;
+            if (m0 + 3 < M && pos + 3 < HW) {           // four terms of one image, all present
+                // plain (cacheable) load: the second pass reads the same values again
+                e = *reinterpret_cast<const f4_dword_aligned*>(x + ((uint64_t)img * C + ch) * HW + pos);
+                if constexpr (SQDEV) {
+                    const f4 d = e - center;
+                    e = d * d;
+                }
+            } else {
+                float el[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t m = m0 + c;
+                    float term = 0.0f;                  // terms beyond M count as +0
+                    if (m < M) {
+                        const uint32_t im = m / HW;
+                        const float y = x[((uint64_t)im * C + ch) * HW + (m - im * HW)];
+                        if constexpr (SQDEV) {
+                            const float d = y - center;
+                            term = d * d;
+                        } else {
+                            term = y;
+                        }
+                    }
+                    el[c] = term;
+                }
+                e = f4{el[0], el[1], el[2], el[3]};
+            }
+            t[j][q] = e;
+        }
+    float s[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float a = 0.0f;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const f4 e = t[j][q];
+            a = a + e.x;
+            a = a + e.y;
+            a = a + e.z;
+            a = a + e.w;
+        }
+        s[j] = a;
+    }
+    const float r0 = s[0] + s[2];                       // stride 128
+    const float r1 = s[1] + s[3];
+    float r = r0 + r1;                                  // stride 64
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) r = r + __shfl_down(r, d, 64);
+    if (h == 0) part[(uint64_t)ch * nblk + blk] = r;
+}
+
+__global__ __launch_bounds__(kBlock) void k_bn_final(const float* __restrict__ part, uint32_t nblk, float fM,
+                                                     float* __restrict__ out)
+{
+    __shared__ float lds[kBlock];
+    const float* pc = part + (uint64_t)blockIdx.x * nblk;
+    float s = 0.0f;
+    for (uint32_t k = threadIdx.x; k < nblk; k += kBlock) s = s + pc[k];      // partials t, t+256, ... in order
+    s = tree256(s, lds);
+    if (threadIdx.x == 0) out[blockIdx.x] = s / fM;
+}
+
+hipError_t launch_bn_batch_stats(hipStream_t s, const float* x, uint32_t B, uint32_t C, uint32_t HW,
+                                 float* mean, float* var, float* part)
+{
+    const uint32_t M = B * HW;
+    const uint32_t nblk = (M + 4095) / 4096;
+    if (C == 0) return hipSuccess;
+    const dim3 grid((nblk + 3) / 4, C);
+    const float fM = (float)M;
+    if (nblk) hipLaunchKernelGGL(k_bn_partials<false>, grid, dim3(kBlock), 0, s, x, C, HW, M, nblk, mean, part);
+    hipLaunchKernelGGL(k_bn_final, dim3(C), dim3(kBlock), 0, s, part, nblk, fM, mean);
+    if (nblk) hipLaunchKernelGGL(k_bn_partials<true>, grid, dim3(kBlock), 0, s, x, C, HW, M, nblk, mean, part);
+    hipLaunchKernelGGL(k_bn_final, dim3(C), dim3(kBlock), 0, s, part, nblk, fM, var);
     return hipGetLastError();
 }
 

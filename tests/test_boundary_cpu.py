@@ -68,6 +68,8 @@ def test_null_handle_is_rejected_everywhere():
     assert B.es_set_option(0, "nontemporal", 1) == B.ES_EINVAL
     assert B.es_stage_fence(0) == B.ES_EINVAL
     assert B.es_grad_sq_norm(0, 0, 0) == B.ES_EINVAL
+    assert B.es_clip_sgd_step(0, 0, 0, 0, 0, 1.0, 0.0, 0.1, 0.9) == B.ES_EINVAL
+    assert B.es_bn_batch_stats(0, 2, 2, 8, 0, 0, 0, 0) == B.ES_EINVAL
     assert B.es_checkpoint_bytes(0) == 0
     assert B.es_checkpoint_export(0, 0, 0, 0, 0, 0) == B.ES_EINVAL
     assert B.es_checkpoint_import(0, 0, 0, 0, 0)[0] == B.ES_EINVAL
