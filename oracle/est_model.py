@@ -116,3 +116,101 @@ class ESTModel:
 
     def est_bn(self, e: int) -> np.ndarray:
         return self.slot_bn[self.worker_of_est[e]][self.slot_of_est[e]]
+
+
+# ---------------------------------------------------------------------------------------------
+# Host-swapped gradient contexts (paper section 3.2: an EST's gradients are copied to host
+# memory when it is switched out; section 5.1.3: the copies overlap with compute).  At the end of
+# the global step the buckets come back one at a time into TWO device buffers: while bucket b is
+# reduced out of one buffer, bucket b+1 is copied into the other.  This is pure data movement:
+# the result has to be the one of reduce_and_update above.  What has to be right is the
+# schedule: which bucket is resident in which buffer when.
+#
+# The schedule is a list of operations for two in-order queues (copy, compute):
+#   ("fill",   b, half, wait)   copy queue:    bucket b of all N ranks -> buffer `half`
+#   ("reduce", b, half, wait)   compute queue: ring-ordered reduce of bucket b out of buffer `half`
+# `wait` is the index (in the list) of the one operation of the OTHER queue that must have
+# finished first, or -1: fill b waits for reduce b-2 (the previous user of its buffer), reduce b
+# waits for fill b.  Operations of one queue run in list order.
+# ---------------------------------------------------------------------------------------------
+def swap_in_schedule(n_buckets: int) -> List[Tuple[str, int, int, int]]:
+    ops: List[Tuple[str, int, int, int]] = []
+    reduce_at = {}
+    for b in range(n_buckets):
+        half = b % 2
+        ops.append(("fill", b, half, reduce_at.get(b - 2, -1)))
+        ops.append(("reduce", b, half, len(ops) - 1))
+        reduce_at[b] = len(ops) - 1
+    return ops
+
+
+def run_swap_in(ops: Sequence[Tuple[str, int, int, int]], host_rows: Callable[[int], np.ndarray],
+                bucket_lens: Sequence[int], n_ranks: int, chunk_align: int,
+                rng: Optional[np.random.Generator] = None) -> List[np.ndarray]:
+    """Executes a schedule on real data under ONE legal interleaving of the two queues (chosen by
+    ``rng``; None = strictly alternating) and returns the averaged gradient per bucket.
+
+    ``host_rows(b)`` returns the (N, L_b) array of the ranks' host-resident gradients of bucket b.
+    A buffer is poisoned (NaN) as soon as its reduce has run, and a fill overwrites whatever the
+    buffer holds, so a schedule that reduces before the fill has finished, or refills a buffer
+    that is still to be read, produces NaNs or another bucket's numbers.  Raises on deadlock."""
+    lmax = max(list(bucket_lens) + [1])
+    bufs = [np.full((n_ranks, lmax), np.nan, dtype=np.float32) for _ in range(2)]
+    holds = [None, None]                          # which bucket each buffer holds now
+    done = [False] * len(ops)
+    out: List[Optional[np.ndarray]] = [None] * len(bucket_lens)
+    queues = {"fill": [i for i, o in enumerate(ops) if o[0] == "fill"],
+              "reduce": [i for i, o in enumerate(ops) if o[0] == "reduce"]}
+    heads = {"fill": 0, "reduce": 0}
+    turn = 0
+    while not all(done):
+        ready = []
+        for q in ("fill", "reduce"):
+            if heads[q] < len(queues[q]):
+                i = queues[q][heads[q]]
+                w = ops[i][3]
+                if w < 0 or done[w]:
+                    ready.append(q)
+        if not ready:
+            raise RuntimeError("schedule deadlocks")
+        if rng is None:
+            q = ready[turn % len(ready)]
+            turn += 1
+        else:
+            q = ready[int(rng.integers(len(ready)))]
+        i = queues[q][heads[q]]
+        kind, b, half, _ = ops[i]
+        L = bucket_lens[b]
+        if kind == "fill":
+            bufs[half][:, :L] = host_rows(b)
+            holds[half] = b
+        else:
+            if holds[half] != b:
+                raise AssertionError(f"reduce of bucket {b} finds bucket {holds[half]} in buffer {half}")
+            out[b] = ring_order_reduce(np.ascontiguousarray(bufs[half][:, :L]), chunk_align)
+            bufs[half][:] = np.nan
+            holds[half] = None
+        done[i] = True
+        heads[q] += 1
+    return out
+
+
+class SwappedESTModel(ESTModel):
+    """ESTModel whose staged gradients live in host memory and come back through the two-buffer
+    schedule at the end of the global step."""
+
+    def reduce_and_update(self, rng: Optional[np.random.Generator] = None, ops=None) -> None:
+        def rows(b):
+            r = np.empty((self.N, self.buckets[b][1]), dtype=np.float32)
+            for e in range(self.N):
+                w, s = self.worker_of_est[e], self.slot_of_est[e]
+                r[e] = self.slot_grad[w][s][b]
+            return r
+        lens = [ln for _, ln in self.buckets]
+        avg = run_swap_in(ops if ops is not None else swap_in_schedule(len(self.buckets)), rows, lens,
+                          self.N, self.A, rng)
+        for b, (off, ln) in enumerate(self.buckets):
+            self.avg[off:off + ln] = avg[b]
+            for e in range(self.N):
+                self.slot_grad[self.worker_of_est[e]][self.slot_of_est[e]][b] = None
+        sgd_momentum(self.p, self.v, self.avg, self.lr, self.mu)

@@ -133,10 +133,13 @@ def run_ddp_reference(sc: Scenario, gen_device="cpu") -> Result:
     return Result(ref.p, ref.v, ref.avg, ref.philox, ref.bn, masks)
 
 
-def run_est_model(sc: Scenario, g: Grouping, regroup_at: Optional[Dict[int, Grouping]] = None) -> Result:
+def run_est_model(sc: Scenario, g: Grouping, regroup_at: Optional[Dict[int, Grouping]] = None,
+                  model_cls=None) -> Result:
     """``regroup_at`` maps a step index to the grouping the job continues with from that
     step on, through an on-demand checkpoint and a fresh model (an elasticity event)."""
     from oracle.est_model import ESTModel
+    if model_cls is not None:
+        ESTModel = model_cls
     N = sc.n_logical
     seeds = [philox_seed(sc, e) for e in range(N)] if sc.mask_n else None
     bn0 = np.stack([bn_init(sc, e).numpy() for e in range(N)]) if sc.bn_len else None
