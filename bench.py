@@ -686,6 +686,68 @@ def measure(torch, a, cid, headline, oracle_leg):
     return res
 
 
+def host_swap_leg(torch, a, cid=2):
+    """Memory-pressure mode (the paper's own placement of EST gradients, section 3.2): gradient slots
+    in pinned host memory.  Two ways of reaching them are timed on one configuration: direct access
+    over the host link from the staging and reduce kernels, and swap-in (device-to-host staging by
+    asynchronous copies, buckets streamed back through two HBM buffers while the previous bucket is
+    reduced).  Priced against the link rate a plain pinned-memory copy reaches in the same process."""
+    from paper_2208_14228_amd import binding as B
+    from paper_2208_14228_amd.job import ESTJob
+    from workloads import configs
+
+    cfg = configs.config(cid)
+    lay, N, P = cfg.layout, cfg.n_logical, cfg.layout.n_params
+    dev = "cuda:0"
+    steps = max(3, min(a.steps, 5))
+    # link rate: plain copies of 1 GiB between pinned host memory and HBM
+    pin = torch.empty(1 << 28, dtype=torch.float32, pin_memory=True)
+    d = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+    link = {}
+    for name, (dst, src) in (("h2d", (d, pin)), ("d2h", (pin, d))):
+        dst.copy_(src, non_blocking=True); torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        link[name] = 3 * 4 * (1 << 28) / (time.perf_counter() - t0) / 1e9
+    del pin, d
+    out = {"note": "gradient slots in pinned host memory (memory-pressure mode); host link, not HBM",
+           "config": cid, "n_logical": N, "n_params": P, "slot_bytes": N * 4 * P,
+           "link_GBps": {k: round(v, 1) for k, v in link.items()}}
+    src = [torch.randn(P, device=dev) * 1e-2 for _ in range(N)]
+    all_buckets = list(range(lay.n_buckets))
+    for mode in ("direct", "swap_in"):
+        job = ESTJob(N, P, lay.buckets, cfg.chunk_align, [], None, None, dev, use_streams="three")
+        job.set_option("host_slots", 1)
+        job.set_option("swap_in", 1 if mode == "swap_in" else 0)
+        job.set_grouping([0] * N, list(range(N)))
+        m = [B.Marshalled(all_buckets, [src[e].data_ptr() + 4 * off for off, _ in lay.buckets]) for e in range(N)]
+        st, rd, wall = [], [], []
+        for i in range(-1, steps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for e in range(N):
+                B.es_accumulate_batch_m(job.h, e, m[e])
+            job.stage.synchronize()
+            t1 = time.perf_counter()
+            job.reduce_sgd_step(cfg.lr, cfg.momentum, store_avg=False)
+            job.sync(); torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            if i >= 0:
+                st.append((t1 - t0) * 1e3); rd.append((t2 - t1) * 1e3); wall.append((t2 - t0) * 1e3)
+        job.close()
+        sm, rm = statistics.fmean(st), statistics.fmean(rd)
+        out[mode] = {"staging_ms": round(sm, 3), "staging_d2h_GBps": round(N * 4 * P / (sm * 1e-3) / 1e9, 1),
+                     "staging_frac_of_link": round(N * 4 * P / (sm * 1e-3) / 1e9 / link["d2h"], 3),
+                     "reduce_ms": round(rm, 3), "reduce_h2d_GBps": round(N * 4 * P / (rm * 1e-3) / 1e9, 1),
+                     "reduce_frac_of_link": round(N * 4 * P / (rm * 1e-3) / 1e9 / link["h2d"], 3),
+                     "step_ms": round(statistics.fmean(wall), 3)}
+    del src
+    torch.cuda.empty_cache()
+    return out
+
+
 def traffic_from_profiles(cid, fused):
     """HBM traffic of the reduce kernel cannot be measured from inside the process: it comes from the
     committed rocprofv3 counter summary of this same command, and only while the kernels are still
@@ -738,6 +800,7 @@ def main():
 
     short = {c: measure(torch, a, c, False, oracle_leg) for c in others}
     ceil = None if a.no_extras else ceilings()
+    host_swap = None if a.no_extras else host_swap_leg(torch, a)
     head = measure(torch, a, a.config, True, oracle_leg)
     switch = None if a.no_switch else est_switch_us(torch)
 
@@ -776,6 +839,7 @@ def main():
         "cpu_baseline_all_cores": head["cpu_baseline_all_cores"],
         "est_switch": switch,
         "ceilings": ceil,
+        "host_swapped_slots": host_swap,
     }
     for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
               "clip_sgd_step", "bn_batch_stats", "checkpoint", "cold_step"):

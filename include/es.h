@@ -434,6 +434,15 @@ int es_sync(es_handle* h);
  *                         workers' gradient arenas are placed in HBM in worker order until
  *                         this many MiB are used; the arenas that no longer fit spill to
  *                         pinned host memory (only what does not fit pays the host link)
+ *   "swap_in"             0/1 (only between global steps, ES_ESTATE otherwise): how host-resident
+ *                         gradient slots are reached.  0: the staging copy and the reduce kernel
+ *                         access the mapped host memory directly over the link.  1: the paper's
+ *                         mechanism - an EST's gradients are staged by asynchronous device-to-host
+ *                         copies (copy engines, the compute units stay free for the next EST), and
+ *                         the reduce streams them back bucket by bucket into two HBM buffers of
+ *                         2 * n_logical * (largest bucket) floats, copying bucket b+1 on the
+ *                         library's own copy queue while bucket b is reduced (es_plan_swap_in);
+ *                         slots that are in HBM are read where they are.  Same bits either way
  *   "slots_on_host"       read-only (es_get_option): ESTs whose gradient slot is on the host
  *   "reduce_tile_elems"   elements of one bucket chunk handled by one workgroup
  *                         (multiple of 4, 256 .. 65536)
@@ -452,6 +461,29 @@ int es_sync(es_handle* h);
  */
 int es_set_option(es_handle* h, const char* name, int64_t value);
 int es_get_option(es_handle* h, const char* name, int64_t* value);
+
+/*
+ * Host-only planning helper (touches no device): the schedule of the swap-in reduce (option
+ * "swap_in"; paper section 3.2 keeps the gradients of switched-out ESTs in host memory, section
+ * 5.1.3 overlaps their copies with compute).  The buckets of all ranks come back one at a time
+ * into TWO device buffers; the list says what the library enqueues, in this order, on its copy
+ * queue (fill) and on main (reduce):
+ *   kind    ES_SWAP_FILL: bucket `bucket` of every host-resident rank -> buffer `half`;
+ *           ES_SWAP_REDUCE: ring-ordered reduce (and update) of that bucket out of buffer `half`
+ *   wait    index in the list of the one operation of the OTHER queue that has to finish first,
+ *           or -1: a fill waits for the reduce that used its buffer before (bucket - 2), a reduce
+ *           for its own fill.  Operations of one queue run in list order.
+ * So bucket b+1 is copied while bucket b is reduced and at most two buckets are resident.
+ *   out     HOST array of `capacity` entries, or NULL to query *n_ops (= 2 * n_buckets) only
+ */
+enum { ES_SWAP_FILL = 0, ES_SWAP_REDUCE = 1 };
+typedef struct es_swap_op {
+    uint32_t kind;
+    uint32_t bucket;
+    uint32_t half;
+    int32_t  wait;
+} es_swap_op;
+int es_plan_swap_in(uint32_t n_buckets, es_swap_op* out, uint64_t capacity, uint64_t* n_ops);
 
 /*
  * Host-only planning helper (touches no device): the work decomposition of the

@@ -38,6 +38,11 @@ DEV_ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_
 DEV_FREE_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p, ctypes.c_void_p)
 
 
+class EsSwapOp(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_uint32), ("bucket", ctypes.c_uint32), ("half", ctypes.c_uint32),
+                ("wait", ctypes.c_int32)]
+
+
 class EsTile(ctypes.Structure):
     _fields_ = [("offset_elems", ctypes.c_uint64), ("len_elems", ctypes.c_uint32),
                 ("start_rank", ctypes.c_uint32)]
@@ -109,6 +114,8 @@ _SIGS = {
     "es_plan_tiles": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(EsBucketLayout), ctypes.c_uint32,
                                      ctypes.c_uint32, ctypes.POINTER(EsTile), ctypes.c_uint64,
                                      ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint64)]),
+    "es_plan_swap_in": (ctypes.c_int, [ctypes.c_uint32, ctypes.POINTER(EsSwapOp), ctypes.c_uint64,
+                                       ctypes.POINTER(ctypes.c_uint64)]),
     "es_query": (ctypes.c_int, [_VP, ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
                                 ctypes.POINTER(ctypes.c_uint64), ctypes.POINTER(ctypes.c_uint32),
                                 ctypes.POINTER(ctypes.c_uint64)]),
@@ -318,6 +325,17 @@ def es_plan_tiles(n_logical: int, n_params: int, buckets, chunk_align: int, tile
     st = lib().es_plan_tiles(n_logical, ctypes.byref(lay), tile_elems, big_unroll, out, nt.value,
                              ctypes.byref(nt), ctypes.byref(nb))
     return st, nb.value, [(t.offset_elems, t.len_elems, t.start_rank) for t in out[:nt.value]]
+
+
+def es_plan_swap_in(n_buckets: int):
+    """Returns (status, [(kind, bucket, half, wait), ...]) with kind "fill" or "reduce"."""
+    n = ctypes.c_uint64()
+    st = lib().es_plan_swap_in(n_buckets, None, 0, ctypes.byref(n))
+    if st:
+        return st, []
+    out = (EsSwapOp * max(1, n.value))()
+    st = lib().es_plan_swap_in(n_buckets, out, n.value, ctypes.byref(n))
+    return st, [("fill" if o.kind == 0 else "reduce", o.bucket, o.half, o.wait) for o in out[:n.value]]
 
 
 def es_query(h):

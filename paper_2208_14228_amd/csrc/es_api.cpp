@@ -69,6 +69,19 @@ struct es_handle {
     uint32_t tile_elems = 2048;
     ReduceShape shape{2, 8, 1, 0, 1, 0};
 
+    // Swap-in of host-resident gradient slots (option "swap_in"): at the reduce the buckets come
+    // back one at a time into two device buffers, bucket b+1 being copied while bucket b is reduced.
+    bool swap_in = false;
+    bool swap_ready = false;                    // tables below match the current grouping and tile shape
+    hipStream_t s_swap = nullptr;               // the library's own copy queue (default priority)
+    hipEvent_t ev_filled[2] = {nullptr, nullptr}, ev_consumed[2] = {nullptr, nullptr};
+    float* d_swap_buf = nullptr;                // 2 x N rows of swap_row floats
+    uint64_t swap_row = 0;
+    Tile* d_swap_tiles = nullptr;               // per-bucket tile tables, back to back
+    std::vector<uint64_t> swap_tile_off;        // first tile of bucket b
+    std::vector<uint32_t> swap_n_tiles, swap_n_big;
+    const float** d_swap_tables = nullptr;      // [half][bucket][rank] gradient base pointers
+
     // the caller's device allocator (es_bucket_layout), or null: hipMalloc / hipFree
     es_dev_alloc_fn dev_alloc = nullptr;
     es_dev_free_fn dev_free = nullptr;
@@ -124,6 +137,14 @@ uint8_t* ctx_base(const es_handle* h, uint32_t est)
 {
     const Worker& w = h->workers[h->worker_of[est]];
     return w.ctx_arena + (uint64_t)h->slot_of[est] * h->ctx_stride;
+}
+
+// Under swap-in, gradients of an EST whose slot lives in host memory are staged by asynchronous
+// device-to-host copies (the copy engines, which leave the compute units to the next EST) instead
+// of a copy kernel that writes through the host link.
+bool dma_staging(const es_handle* h, uint32_t est)
+{
+    return h->swap_in && h->workers[h->worker_of[est]].grad_on_host;
 }
 
 void free_worker(es_handle* h, Worker& w)
@@ -218,6 +239,7 @@ int build_tiles(es_handle* h)
     const uint64_t TB = h->shape.big_unroll ? (uint64_t)kReduceBlock * h->shape.big_unroll * 4 : 0;
     plan_tiles(h->buckets, h->N, h->A, h->tile_elems, TB, big, tiles);
     if (big.size() + tiles.size() > 0x7fffffffull) return ES_EINVAL;
+    h->swap_ready = false;                       // the per-bucket tile tables of the swap-in path follow the same shape
     h->n_big = (uint32_t)big.size();
     big.insert(big.end(), tiles.begin(), tiles.end());
     tiles.swap(big);
@@ -293,6 +315,7 @@ int sync_all(es_handle* h)
     ES_HIP(h, hipStreamSynchronize(h->s_main));
     if (h->s_ctx != h->s_main) ES_HIP(h, hipStreamSynchronize(h->s_ctx));
     if (h->s_stage != h->s_main && h->s_stage != h->s_ctx) ES_HIP(h, hipStreamSynchronize(h->s_stage));
+    if (h->s_swap) ES_HIP(h, hipStreamSynchronize(h->s_swap));
     h->stage_pending = false;
     return ES_OK;
 }
@@ -333,6 +356,133 @@ struct DeviceGuard {
     DeviceGuard(const DeviceGuard&) = delete;
     DeviceGuard& operator=(const DeviceGuard&) = delete;
 };
+
+// The two-buffer swap-in schedule: what is enqueued, in this order, on the copy queue ("fill")
+// and on main ("reduce"), and the one operation of the other queue each has to wait for.
+void swap_plan(uint32_t n_buckets, std::vector<es_swap_op>& ops)
+{
+    ops.clear();
+    std::vector<int32_t> reduce_at(n_buckets, -1);
+    for (uint32_t b = 0; b < n_buckets; ++b) {
+        es_swap_op f;
+        f.kind = ES_SWAP_FILL; f.bucket = b; f.half = b & 1;
+        f.wait = b >= 2 ? reduce_at[b - 2] : -1;                  // the previous user of this buffer
+        ops.push_back(f);
+        es_swap_op r;
+        r.kind = ES_SWAP_REDUCE; r.bucket = b; r.half = b & 1;
+        r.wait = (int32_t)ops.size() - 1;                         // its own fill
+        ops.push_back(r);
+        reduce_at[b] = (int32_t)ops.size() - 1;
+    }
+}
+
+void swap_release(es_handle* h)
+{
+    dev_release(h, h->d_swap_buf);        h->d_swap_buf = nullptr;
+    dev_release(h, h->d_swap_tiles);      h->d_swap_tiles = nullptr;
+    dev_release(h, (void*)h->d_swap_tables); h->d_swap_tables = nullptr;
+    h->swap_ready = false;
+}
+
+// Device buffers, per-bucket tile tables and per-bucket pointer tables of the swap-in path.
+int swap_prepare(es_handle* h)
+{
+    if (h->swap_ready) return ES_OK;
+    swap_release(h);
+    if (!h->s_swap) {
+        ES_HIP(h, hipStreamCreateWithFlags(&h->s_swap, hipStreamNonBlocking));
+        for (int k = 0; k < 2; ++k) {
+            ES_HIP(h, hipEventCreateWithFlags(&h->ev_filled[k], hipEventDisableTiming));
+            ES_HIP(h, hipEventCreateWithFlags(&h->ev_consumed[k], hipEventDisableTiming));
+        }
+    }
+    const size_t nb = h->buckets.size();
+    uint64_t lmax = 0;
+    for (const es_bucket& b : h->buckets) lmax = std::max<uint64_t>(lmax, b.len_elems);
+    // a row starts as far into a 128-byte line as its bucket does in the flat space, so the tile
+    // planner's line alignment holds in the buffer too
+    h->swap_row = round_up(lmax + 32, 64);
+    if (lmax) ES_HIP(h, dev_malloc(h, (void**)&h->d_swap_buf, 2 * (uint64_t)h->N * h->swap_row * sizeof(float)));
+    std::vector<Tile> all;
+    h->swap_tile_off.assign(nb, 0);
+    h->swap_n_tiles.assign(nb, 0);
+    h->swap_n_big.assign(nb, 0);
+    const uint64_t TB = h->shape.big_unroll ? (uint64_t)kReduceBlock * h->shape.big_unroll * 4 : 0;
+    for (size_t b = 0; b < nb; ++b) {
+        std::vector<Tile> big, small;
+        plan_tiles(std::vector<es_bucket>(1, h->buckets[b]), h->N, h->A, h->tile_elems, TB, big, small);
+        h->swap_tile_off[b] = all.size();
+        h->swap_n_big[b] = (uint32_t)big.size();
+        h->swap_n_tiles[b] = (uint32_t)(big.size() + small.size());
+        all.insert(all.end(), big.begin(), big.end());
+        all.insert(all.end(), small.begin(), small.end());
+    }
+    if (!all.empty()) {
+        ES_HIP(h, dev_malloc(h, (void**)&h->d_swap_tiles, all.size() * sizeof(Tile)));
+        ES_HIP(h, hipMemcpy(h->d_swap_tiles, all.data(), all.size() * sizeof(Tile), hipMemcpyHostToDevice));
+    }
+    // rank r, bucket b, buffer `half`: the kernel forms table[r] + (flat offset), so a row's entry
+    // is its start minus the bucket's flat offset; a rank whose slot is in HBM is read where it is
+    std::vector<const float*> tab(2 * nb * h->N);
+    for (int half = 0; half < 2; ++half)
+        for (size_t b = 0; b < nb; ++b)
+            for (uint32_t r = 0; r < h->N; ++r) {
+                const Worker& w = h->workers[h->worker_of[r]];
+                const float* entry = slot_base(h, r);
+                if (w.grad_on_host) {
+                    const uintptr_t row = (uintptr_t)(h->d_swap_buf + ((uint64_t)half * h->N + r) * h->swap_row +
+                                                      (h->buckets[b].offset_elems & 31));
+                    entry = (const float*)(row - h->buckets[b].offset_elems * sizeof(float));
+                }
+                tab[((size_t)half * nb + b) * h->N + r] = entry;
+            }
+    if (!tab.empty()) {
+        ES_HIP(h, dev_malloc(h, (void**)&h->d_swap_tables, tab.size() * sizeof(float*)));
+        ES_HIP(h, hipMemcpy((void*)h->d_swap_tables, tab.data(), tab.size() * sizeof(float*), hipMemcpyHostToDevice));
+    }
+    h->swap_ready = true;
+    return ES_OK;
+}
+
+// The reduce of a job whose gradient slots (some or all) are in host memory, with swap-in.
+int swap_reduce(es_handle* h, float* avg, float* p, float* v, float lr, float mu)
+{
+    int rc = swap_prepare(h);
+    if (rc != ES_OK) return rc;
+    const size_t nb = h->buckets.size();
+    // the copy queue starts after every staging copy of the step and after main (in-place sources)
+    if ((rc = order_after(h, h->s_swap, h->s_stage, h->ev_stage)) != ES_OK) return rc;
+    if ((rc = order_after(h, h->s_swap, h->s_main, h->ev_main)) != ES_OK) return rc;
+    h->stage_pending = false;
+    std::vector<const float*> in_place(h->N, nullptr);
+    for (size_t k = 0; k < h->in_place_rank.size(); ++k) in_place[h->in_place_rank[k]] = h->in_place_ptr[k];
+    std::vector<es_swap_op> ops;
+    swap_plan((uint32_t)nb, ops);
+    for (const es_swap_op& op : ops) {
+        const es_bucket& bk = h->buckets[op.bucket];
+        if (op.kind == ES_SWAP_FILL) {
+            if (op.wait >= 0) ES_HIP(h, hipStreamWaitEvent(h->s_swap, h->ev_consumed[op.half], 0));
+            for (uint32_t r = 0; r < h->N && bk.len_elems; ++r) {
+                const Worker& w = h->workers[h->worker_of[r]];
+                const float* src = (in_place[r] ? in_place[r] : slot_base(h, r)) + bk.offset_elems;
+                float* dst = w.grad_on_host
+                                 ? h->d_swap_buf + ((uint64_t)op.half * h->N + r) * h->swap_row + (bk.offset_elems & 31)
+                                 : slot_base(h, r) + bk.offset_elems;
+                if (src == dst) continue;                       // a rank resident in HBM, read where it is
+                ES_HIP(h, hipMemcpyAsync(dst, src, bk.len_elems * sizeof(float), hipMemcpyDefault, h->s_swap));
+            }
+            ES_HIP(h, hipEventRecord(h->ev_filled[op.half], h->s_swap));
+        } else {
+            ES_HIP(h, hipStreamWaitEvent(h->s_main, h->ev_filled[op.half], 0));
+            ES_HIP(h, launch_ring_reduce(h->s_main, h->d_swap_tiles + h->swap_tile_off[op.bucket],
+                                         h->swap_n_tiles[op.bucket], h->swap_n_big[op.bucket],
+                                         h->d_swap_tables + ((size_t)op.half * nb + op.bucket) * h->N, h->N,
+                                         avg, p, v, lr, mu, h->shape));
+            ES_HIP(h, hipEventRecord(h->ev_consumed[op.half], h->s_main));
+        }
+    }
+    return ES_OK;
+}
 
 }  // namespace
 
@@ -413,6 +563,15 @@ int es_destroy(es_handle* h)
     dev_release(h, h->d_tiles);
     dev_release(h, (void*)h->d_slots);
     dev_release(h, h->d_partials);
+    swap_release(h);
+    if (h->s_swap) {
+        (void)hipStreamSynchronize(h->s_swap);
+        (void)hipStreamDestroy(h->s_swap);
+    }
+    for (int k = 0; k < 2; ++k) {
+        if (h->ev_filled[k]) (void)hipEventDestroy(h->ev_filled[k]);
+        if (h->ev_consumed[k]) (void)hipEventDestroy(h->ev_consumed[k]);
+    }
     if (h->ev_main) (void)hipEventDestroy(h->ev_main);
     if (h->ev_ctx) (void)hipEventDestroy(h->ev_ctx);
     if (h->ev_stage) (void)hipEventDestroy(h->ev_stage);
@@ -462,6 +621,20 @@ try {
     return ES_ENOMEM;
 }
 
+int es_plan_swap_in(uint32_t n_buckets, es_swap_op* out, uint64_t capacity, uint64_t* n_ops)
+try {
+    std::vector<es_swap_op> ops;
+    swap_plan(n_buckets, ops);
+    if (n_ops) *n_ops = ops.size();
+    if (out) {
+        if (capacity < ops.size()) return ES_EINVAL;
+        std::copy(ops.begin(), ops.end(), out);
+    }
+    return ES_OK;
+} catch (const std::bad_alloc&) {
+    return ES_ENOMEM;
+}
+
 int es_set_grouping(es_handle* h, uint32_t n_workers, const uint32_t* worker_of_est,
                     const uint32_t* slot_of_est)
 try {
@@ -501,6 +674,7 @@ try {
     h->workers.swap(fresh);
     h->worker_of.assign(worker_of_est, worker_of_est + h->N);
     h->slot_of.assign(slot_of_est, slot_of_est + h->N);
+    h->swap_ready = false;                       // slot addresses and placements have changed
     return upload_slot_table(h);
 } catch (const std::bad_alloc&) {
     return ES_ENOMEM;
@@ -611,7 +785,10 @@ int es_accumulate(es_handle* h, uint32_t est, uint32_t bucket, const float* d_gr
         if (a < b + n && b < a + n) return ES_EINVAL;
         int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
         if (rc != ES_OK) return rc;
-        ES_HIP(h, launch_copy_f32(h->s_stage, dst, d_grad_bucket, len));
+        if (dma_staging(h, est))
+            ES_HIP(h, hipMemcpyAsync(dst, d_grad_bucket, len * sizeof(float), hipMemcpyDeviceToHost, h->s_stage));
+        else
+            ES_HIP(h, launch_copy_f32(h->s_stage, dst, d_grad_bucket, len));
         h->stage_pending = true;
     }
     flag = 1;
@@ -694,6 +871,20 @@ void collect_runs(es_handle* h, uint32_t est, uint32_t n, const uint32_t* bucket
     }
 }
 
+int enqueue_staging(es_handle* h, const RunBuilder& rb, bool dma, size_t first_launch = 0)
+{
+    for (size_t k = first_launch; k < rb.launches.size(); ++k) {
+        const CopyRuns& r = rb.launches[k];
+        if (!dma) {
+            ES_HIP(h, launch_copy_runs(h->s_stage, r));
+            continue;
+        }
+        for (uint32_t j = 0; j < r.n_runs; ++j)
+            ES_HIP(h, hipMemcpyAsync(r.dst[j], r.src[j], r.n[j] * sizeof(float), hipMemcpyDeviceToHost, h->s_stage));
+    }
+    return ES_OK;
+}
+
 void mark_batch(es_handle* h, uint32_t est, uint32_t n, const uint32_t* buckets)
 {
     const size_t nb = h->buckets.size();
@@ -714,7 +905,7 @@ try {
     collect_runs(h, est, n, buckets, d_grad_buckets, rb);
     if (!rb.launches.empty()) {
         if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;
-        for (const CopyRuns& r : rb.launches) ES_HIP(h, launch_copy_runs(h->s_stage, r));
+        if ((rc = enqueue_staging(h, rb, dma_staging(h, est))) != ES_OK) return rc;
         h->stage_pending = true;
     }
     mark_batch(h, est, n, buckets);
@@ -741,13 +932,15 @@ try {
             if (h->accumulated[(size_t)e * nb + b]) return ES_ESTATE;
         if (h->P && src != slot_base(h, e) && overlap(src, slot_base(h, e), vec_bytes)) return ES_EINVAL;
     }
-    RunBuilder rb;
+    RunBuilder rb, rb_dma;
     for (uint32_t k = 0; k < n_ests; ++k)
-        if (h->P && d_flat_grads[k] != slot_base(h, ests[k])) rb.add(slot_base(h, ests[k]), d_flat_grads[k], h->P);
-    if (!rb.launches.empty()) {
+        if (h->P && d_flat_grads[k] != slot_base(h, ests[k]))
+            (dma_staging(h, ests[k]) ? rb_dma : rb).add(slot_base(h, ests[k]), d_flat_grads[k], h->P);
+    if (!rb.launches.empty() || !rb_dma.launches.empty()) {
         int rc = order_after(h, h->s_stage, h->s_main, h->ev_main);
+        if (rc == ES_OK) rc = enqueue_staging(h, rb, false);
+        if (rc == ES_OK) rc = enqueue_staging(h, rb_dma, true);
         if (rc != ES_OK) return rc;
-        for (const CopyRuns& r : rb.launches) ES_HIP(h, launch_copy_runs(h->s_stage, r));
         h->stage_pending = true;
     }
     for (uint32_t k = 0; k < n_ests; ++k)
@@ -777,10 +970,14 @@ try {
         // after the outgoing EST's compute on main and after earlier context traffic on the ctx stream
         if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;
         if (h->s_ctx != h->s_main && (rc = order_after(h, h->s_stage, h->s_ctx, h->ev_ctx)) != ES_OK) return rc;
+        const bool dma = dma_staging(h, est_out);
+        RunBuilder none;
+        none.open();
         if (rb.launches.empty()) rb.open();
-        ES_HIP(h, launch_est_boundary(h->s_stage, rb.launches[0], w.d_pieces, n_pieces, ctx_base(h, est_out),
-                                      has_in ? ctx_base(h, est_in) : nullptr, has_in ? kSwitch : kSave));
-        for (size_t k = 1; k < rb.launches.size(); ++k) ES_HIP(h, launch_copy_runs(h->s_stage, rb.launches[k]));
+        ES_HIP(h, launch_est_boundary(h->s_stage, dma ? none.launches[0] : rb.launches[0], w.d_pieces, n_pieces,
+                                      ctx_base(h, est_out), has_in ? ctx_base(h, est_in) : nullptr,
+                                      has_in ? kSwitch : kSave));
+        if ((rc = enqueue_staging(h, rb, dma, dma ? 0 : 1)) != ES_OK) return rc;
         h->stage_pending = true;
     }
     mark_batch(h, est_out, n, buckets);
@@ -862,6 +1059,17 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
             const uintptr_t b = (uintptr_t)o;
             if (o && g < b + sz && b < g + sz) return ES_EINVAL;
         }
+    }
+    bool any_on_host = false;
+    for (const Worker& w : h->workers) any_on_host = any_on_host || w.grad_on_host;
+    if (h->swap_in && any_on_host) {
+        int src = swap_reduce(h, avg, p, v, lr, mu);
+        if (src != ES_OK) return src;
+        std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
+        h->n_accumulated = 0;
+        h->in_place_rank.clear();
+        h->in_place_ptr.clear();
+        return ES_OK;
     }
     int rc = es_stage_fence(h);
     if (rc != ES_OK) return rc;
@@ -1101,6 +1309,15 @@ try {
         h->shape.nontemporal = (int)value;
         return ES_OK;
     }
+    if (k == "swap_in") {
+        if (value != 0 && value != 1) return ES_EINVAL;
+        if (h->n_accumulated != 0) return ES_ESTATE;     // staged gradients would be read the other way
+        int rc = sync_all(h);
+        if (rc != ES_OK) return rc;
+        h->swap_in = value != 0;
+        if (!h->swap_in) swap_release(h);
+        return ES_OK;
+    }
     if (k == "host_slots") {
         if (value != 0 && value != 1) return ES_EINVAL;
         h->host_slots = value != 0;
@@ -1131,6 +1348,7 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "nontemporal") *value = h->shape.nontemporal;
     else if (k == "nontemporal_pv") *value = h->shape.nontemporal_pv;
     else if (k == "host_slots") *value = h->host_slots ? 1 : 0;
+    else if (k == "swap_in") *value = h->swap_in ? 1 : 0;
     else if (k == "hbm_slot_budget_mib") *value = h->hbm_budget_mib;
     else if (k == "slots_on_host") {             // read-only: ESTs whose gradient slot is in host memory now
         int64_t n = 0;

@@ -769,3 +769,80 @@ def test_every_est_taken_in_place():
             S.assert_same(G.collect(sc, job, {}), ref, f"all {N} in place")
         finally:
             job.close()
+
+
+def test_swap_in_of_host_resident_gradient_slots():
+    """The paper's placement of EST gradients (section 3.2) with the swap-in reduce: device-to-host
+    staging by asynchronous copies, buckets streamed back through two HBM buffers while the previous
+    bucket is reduced.  All slots on the host, some on the host, in-place ESTs, every way of staging,
+    odd bucket offsets, big tiles, a regrouping between steps: always the reference's bits."""
+    N = 6
+    lay = buckets.custom([3 * 4096 + 37, 0, 3, 4096, 1001, 4 * N + 1, 20000 + N, 40000, 5], fan_in=9)
+    sc = S.Scenario(N, lay, 1, 0x5A1, steps=3, mask_n=64, bn_channels=(8, 3))
+    ref = S.run_ddp_reference(sc)
+    g = configs.contiguous([2, 4])
+    for flow in ("per_bucket", "boundary", "many", "big_tiles"):
+        job = G.make_job(sc, configs.contiguous([N]),
+                         options={"reduce_big_unroll": 8} if flow == "big_tiles" else None)
+        try:
+            job.set_option("host_slots", 1)
+            job.set_option("swap_in", 1)
+            job.set_grouping(g.worker_of_est, g.slot_of_est)
+            assert B.es_get_option(job.h, "slots_on_host") == (0, N)
+            G.init_contexts(sc, job)
+            masks = {}
+            G.run_steps(sc, job, g, fused=(flow != "per_bucket"), masks=masks, boundary=(flow == "boundary"),
+                        many=(4 if flow == "many" else 0))
+            S.assert_same(G.collect(sc, job, masks), ref, f"swap-in {flow}")
+        finally:
+            job.close()
+    # some arenas in HBM, some on the host; regrouped (and the option switched) between steps
+    sc2 = S.Scenario(N, lay, 4, 0x5A2, steps=3)
+    ref2 = S.run_ddp_reference(sc2)
+    g3 = configs.contiguous([2, 2, 2])
+    job = G.make_job(sc2, configs.contiguous([N]))
+    try:
+        per_worker_mib = 2 * lay.n_params * 4 / 2 ** 20
+        job.set_option("hbm_slot_budget_mib", int(per_worker_mib) + 1)      # one arena of three fits
+        job.set_option("swap_in", 1)
+        job.set_grouping(g3.worker_of_est, g3.slot_of_est)
+        assert B.es_get_option(job.h, "slots_on_host") == (0, 4)
+        G.init_contexts(sc2, job)
+        G.run_steps(sc2, job, g3, fused=True, steps=[0])
+        assert B.es_set_option(job.h, "swap_in", 0) == B.ES_OK             # direct access over the link
+        G.run_steps(sc2, job, g3, fused=False, steps=[1])
+        job.set_option("swap_in", 1)
+        job.set_grouping(g.worker_of_est, g.slot_of_est)                    # tables follow the new slots
+        G.run_steps(sc2, job, g, fused=True, steps=[2])
+        S.assert_same(G.collect(sc2, job, {}), ref2, "mixed placement")
+    finally:
+        job.close()
+    # in-place ESTs under swap-in, and the option refused while gradients are staged
+    sc3 = S.Scenario(4, lay, 4, 0x5A3, steps=2)
+    ref3 = S.run_ddp_reference(sc3)
+    job = G.make_job(sc3, configs.contiguous([4]))
+    try:
+        job.set_option("host_slots", 1)
+        job.set_option("swap_in", 1)
+        job.set_grouping([0, 0, 1, 1], [0, 1, 0, 1])
+        G.init_contexts(sc3, job)
+        for t in range(sc3.steps):
+            flats = []
+            with job.stream_ctx():
+                for e in range(4):
+                    flat = torch.empty(lay.n_params, dtype=torch.float32, device=G.DEV)
+                    for b, (off, ln) in enumerate(lay.buckets):
+                        synth.gradient(lay, b, sc3.seed, t, e, G.DEV, out=flat[off:off + ln])
+                    flats.append(flat)
+            for e in range(4):
+                if e % 2:
+                    job.accumulate_in_place(e, flats[e])
+                else:
+                    job.accumulate_batch(e, list(range(lay.n_buckets)), [flats[e][o:o + l] for o, l in lay.buckets])
+            assert B.es_set_option(job.h, "swap_in", 0) == B.ES_ESTATE
+            job.reduce_sgd_step(sc3.lr, sc3.momentum, store_avg=True)
+            job.sync()
+            torch.cuda.synchronize()
+        S.assert_same(G.collect(sc3, job, {}), ref3, "in place under swap-in")
+    finally:
+        job.close()

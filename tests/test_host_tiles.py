@@ -91,3 +91,27 @@ def test_only_the_first_tile_of_a_chunk_may_start_unaligned():
             assert unaligned_chunks > 0                       # the case is really exercised
             if big:
                 assert n_big * 256 * big * 4 > 0.5 * lay.n_params
+
+
+def test_swap_in_plan_is_the_oracle_models_schedule():
+    """es_plan_swap_in (what the library enqueues for host-resident slots) against the oracle-side
+    model: the same list, and executed by the model under random interleavings it gives the plain
+    reduce."""
+    import numpy as np
+
+    import oracle
+    from oracle.est_model import run_swap_in, swap_in_schedule
+    for n in range(0, 12):
+        st, plan = B.es_plan_swap_in(n)
+        assert st == B.ES_OK and plan == swap_in_schedule(n), n
+    rng = np.random.default_rng(8)
+    lens = [37, 0, 4, 1000, 1, 513, 64, 9]
+    rows = [rng.standard_normal((5, L)).astype(np.float32) for L in lens]
+    _, plan = B.es_plan_swap_in(len(lens))
+    for seed in range(10):
+        got = run_swap_in(plan, lambda b: rows[b], lens, 5, 4, np.random.default_rng(seed))
+        for b, L in enumerate(lens):
+            want = oracle.ring_order_reduce(rows[b], 4)
+            assert np.array_equal(got[b].view(np.uint32), want.view(np.uint32)), (seed, b)
+    n = B.ctypes.c_uint64()
+    assert B.lib().es_plan_swap_in(3, (B.EsSwapOp * 2)(), 2, B.ctypes.byref(n)) == B.ES_EINVAL   # capacity too small
