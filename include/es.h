@@ -449,6 +449,9 @@ int es_sync(es_handle* h);
  *   "reduce_unroll"       16-byte vectors per lane in flight per rank (1, 2, 4)
  *   "reduce_rank_batch"   ranks loaded before their adds are issued (1, 2, 4, 8, 16;
  *                         default 8, or the largest power of two <= n_logical below that)
+ *   "reduce_lds_pad_kib"  -1 (default) or 0 .. 160: KiB of LDS a workgroup of the small-tile reduce
+ *                         reserves without using it, which caps the workgroups resident per CU
+ *                         (160 KiB per CU); -1 = 64 (2 per CU), or 53 (3 per CU) below 4 ranks
  *   "nontemporal"         0/1: streaming hint on gradient loads
  *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the fused
  *                         update (default: 1 if both vectors together exceed 284 MiB, else 0)

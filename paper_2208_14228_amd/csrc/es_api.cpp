@@ -67,7 +67,7 @@ struct es_handle {
     int64_t hbm_budget_mib = -1;                // >= 0: gradient arenas beyond this many MiB of HBM go to the host
     uint64_t hbm_grad_bytes = 0;                // HBM held by gradient arenas allocated in the current regrouping
     uint32_t tile_elems = 2048;
-    ReduceShape shape{2, 8, 1, 0, 1, 0};
+    ReduceShape shape{2, 8, 1, 0, 1, 0, -1};
 
     // Swap-in of host-resident gradient slots (option "swap_in"): at the reduce the buckets come
     // back one at a time into two device buffers, bucket b+1 being copied while bucket b is reduced.
@@ -1294,6 +1294,11 @@ try {
         if (rc != ES_OK) { field = old; (void)build_tiles(h); }
         return rc;
     }
+    if (k == "reduce_lds_pad_kib") {
+        if (value < -1 || value > 160) return ES_EINVAL;
+        h->shape.lds_pad_kib = (int)value;
+        return ES_OK;
+    }
     if (k == "reduce_unroll") {
         if (value != 1 && value != 2 && value != 4) return ES_EINVAL;
         h->shape.unroll = (int)value;
@@ -1347,6 +1352,7 @@ int es_get_option(es_handle* h, const char* name, int64_t* value)
     else if (k == "reduce_rank_batch") *value = h->shape.rank_batch;
     else if (k == "nontemporal") *value = h->shape.nontemporal;
     else if (k == "nontemporal_pv") *value = h->shape.nontemporal_pv;
+    else if (k == "reduce_lds_pad_kib") *value = h->shape.lds_pad_kib;
     else if (k == "host_slots") *value = h->host_slots ? 1 : 0;
     else if (k == "swap_in") *value = h->swap_in ? 1 : 0;
     else if (k == "hbm_slot_budget_mib") *value = h->hbm_budget_mib;

@@ -35,6 +35,19 @@ constexpr uint32_t kBlock = 256;
 #endif
 constexpr uint32_t kReduceBlock = ES_REDUCE_BLOCK;   // lanes per workgroup of the ring-ordered reduce
 constexpr int kBigEpilogue = 16;                     // vectors per lane per pass of a big tile's update epilogue
+
+// Occupancy caps.  Measured on MI355X: the streaming kernels reach more of the HBM rate when a CU
+// has about 64-128 KiB of loads in flight than when it has several times that (more resident
+// workgroups = more DRAM regions open at once).  A launch reserves LDS it never touches so that
+// only 160 KiB / reserve workgroups fit a CU: 2 for the small-tile reduce (3 below 4 ranks, where
+// a workgroup has fewer loads in flight): +4-8 % at N = 2..10 on 26 M and 109 M parameters with
+// nothing cache-resident; 2 for the update and norm kernels: +4 % at 355 M parameters.
+constexpr uint32_t kAuxLdsPad = 64u << 10;
+inline uint32_t reduce_lds_pad(int option_kib, uint32_t n_ranks)
+{
+    if (option_kib >= 0) return (uint32_t)option_kib << 10;
+    return (n_ranks < 4 ? 53u : 64u) << 10;
+}
 constexpr uint32_t kCopyBlock = ES_COPY_BLOCK;   // lanes per workgroup of the batched staging copy
 
 // Entries of the rank -> gradient-base table that are redirected for one reduce
@@ -55,6 +68,8 @@ struct ReduceShape {
     int big_unroll;    // 0, or vectors per lane of a big tile (8, 16, 32): see k_ring_reduce_big
     int big_rank_batch;
     int nontemporal_pv; // streaming hint on parameter / momentum traffic of the fused update
+    int lds_pad_kib = -1; // KiB of LDS reserved (and never touched) per workgroup of the small-tile kernel, to cap the
+                          // workgroups resident per CU; -1 = default for the rank count (see reduce_lds_pad)
 };
 
 // ring-ordered N-way reduce (+ optional fused SGD-momentum).

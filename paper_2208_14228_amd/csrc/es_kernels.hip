@@ -317,12 +317,12 @@ __global__ __launch_bounds__(kReduceBlock) void k_ring_reduce_big(const Tile* ti
 template <int U, int NB>
 static hipError_t launch_reduce_unb(hipStream_t s, const Tile* tiles, uint32_t n_tiles,
                                     const float* const* slots, uint32_t N, float* avg, float* p,
-                                    float* v, float lr, float mu, int nt)
+                                    float* v, float lr, float mu, int nt, uint32_t lds_pad)
 {
     const bool sgd = p != nullptr;
     dim3 grid(n_tiles), block(kReduceBlock);
 #define ES_LAUNCH(NTV, SGDV) \
-    hipLaunchKernelGGL((k_ring_reduce<U, NB, NTV, SGDV>), grid, block, 0, s, tiles, slots, N, avg, p, v, lr, mu)
+    hipLaunchKernelGGL((k_ring_reduce<U, NB, NTV, SGDV>), grid, block, lds_pad, s, tiles, slots, N, avg, p, v, lr, mu)
     if (!sgd) {
         if (nt & 1) ES_LAUNCH(1, false); else ES_LAUNCH(0, false);
     } else {
@@ -344,11 +344,11 @@ static hipError_t launch_reduce_u(hipStream_t s, const Tile* tiles, uint32_t n_t
 {
     const int nt = (sh.nontemporal ? 1 : 0) | (sh.nontemporal_pv ? 2 : 0);
     switch (sh.rank_batch) {
-    case 1:  return launch_reduce_unb<U, 1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
-    case 2:  return launch_reduce_unb<U, 2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
-    case 4:  return launch_reduce_unb<U, 4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
-    case 8:  return launch_reduce_unb<U, 8>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
-    case 16: return launch_reduce_unb<U, 16>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt);
+    case 1:  return launch_reduce_unb<U, 1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N));
+    case 2:  return launch_reduce_unb<U, 2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N));
+    case 4:  return launch_reduce_unb<U, 4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N));
+    case 8:  return launch_reduce_unb<U, 8>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N));
+    case 16: return launch_reduce_unb<U, 16>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N));
     default: return hipErrorInvalidValue;
     }
 }
@@ -481,7 +481,7 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
     const uint64_t nvec = n >> 2;
     uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
     if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(k_sgd, dim3((uint32_t)blocks), dim3(kBlock), 0, s, p, v, g, n, lr, mu);
+    hipLaunchKernelGGL(k_sgd, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, lr, mu);
     return hipGetLastError();
 }
 
@@ -541,7 +541,7 @@ hipError_t launch_sgd_clip(hipStream_t s, float* p, float* v, const float* g, ui
     const uint64_t nvec = n >> 2;
     uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
     if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(k_sgd_clip, dim3((uint32_t)blocks), dim3(kBlock), 0, s, p, v, g, n, norm2, max_norm,
+    hipLaunchKernelGGL(k_sgd_clip, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, norm2, max_norm,
                        eps, lr, mu);
     return hipGetLastError();
 }
@@ -655,7 +655,7 @@ __global__ __launch_bounds__(kBlock) void k_sq_final(const float* __restrict__ p
 hipError_t launch_sq_norm(hipStream_t s, const float* x, uint64_t n, float* part, float* out)
 {
     const uint64_t nblk = (n + 4095) / 4096;
-    if (nblk) hipLaunchKernelGGL(k_sq_partials, dim3((uint32_t)((nblk + 3) / 4)), dim3(kBlock), 0, s, x, n, nblk, part);
+    if (nblk) hipLaunchKernelGGL(k_sq_partials, dim3((uint32_t)((nblk + 3) / 4)), dim3(kBlock), kAuxLdsPad, s, x, n, nblk, part);
     hipLaunchKernelGGL(k_sq_final, dim3(1), dim3(kBlock), 0, s, part, nblk, out);
     return hipGetLastError();
 }
