@@ -52,7 +52,8 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle legs (no zero_ulp either)")
     ap.add_argument("--no-switch", action="store_true", help="skip the EST-switch timing")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the variant legs (in-place, zero-copy, graph, norm, checkpoint, ceilings)")
+                    help="skip every leg but the timed step (no cache-swept reduce, in-place, zero-copy, graph, "
+                         "norm, checkpoint, host-swap, ceilings)")
     ap.add_argument("--streams", choices=["one", "two", "three"], default="one",
                     help="one in-order stream (default: nothing to overlap with in this benchmark) or "
                          "separate main/ctx/stage streams wired with events")
@@ -474,7 +475,7 @@ def measure(torch, a, cid, headline, oracle_leg):
     # launch.  Only where parameters and momentum would fit it; both cache policies. ----
     slot_ptrs = [[B.es_grad_slot(job.h, e, b) for b in all_buckets] for e in range(N)]
     slot_m = [B.Marshalled(all_buckets, slot_ptrs[e]) for e in range(N)]
-    if fused and 2 * 4 * P <= CACHE_FIT_BYTES and not a.host_slots:
+    if fused and 2 * 4 * P <= CACHE_FIT_BYTES and not a.host_slots and not a.no_extras:
         sweep = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         cold = {}
         for nt_pv in (0, 1):
@@ -663,7 +664,7 @@ def measure(torch, a, cid, headline, oracle_leg):
 
     # small working sets live in the 256 MB Infinity Cache between steps: also time the whole
     # step cold, after a 1 GiB fill has swept the cache (per-step HIP events, fill not timed)
-    if (2 * N + 3) * 4 * P < (512 << 20):
+    if (2 * N + 3) * 4 * P < (512 << 20) and not a.no_extras:
         sweep = torch.empty(1 << 28, dtype=torch.float32, device=dev)
         tot = []
         for _ in range(steps):
