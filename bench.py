@@ -800,6 +800,17 @@ def main():
         oracle_leg = OracleLeg(torch, need)
 
     short = {c: measure(torch, a, c, False, oracle_leg) for c in others}
+    # the same step of the context-heavy configuration with separate main / ctx / stage streams wired
+    # by events (the save of a worker's last EST then overlaps the reduce): what the hand-offs cost
+    three = None
+    if not a.no_extras and a.streams == "one" and not a.no_configs:
+        import copy
+        a3 = copy.copy(a)
+        a3.streams, a3.no_cpu, a3.no_extras = "three", True, True
+        r3 = measure(torch, a3, 4, False, None)
+        three = {"note": "configuration 4 with separate main, ctx and stage streams (events between them) "
+                         "instead of one in-order stream", "ms_per_step": r3["ms_per_step"],
+                 "step_GBps": r3["step_GBps"], "one_stream_ms_per_step": short[4]["ms_per_step"] if 4 in short else None}
     ceil = None if a.no_extras else ceilings()
     host_swap = None if a.no_extras else host_swap_leg(torch, a)
     head = measure(torch, a, a.config, True, oracle_leg)
@@ -841,6 +852,7 @@ def main():
         "est_switch": switch,
         "ceilings": ceil,
         "host_swapped_slots": host_swap,
+        "three_stream_step": three,
     }
     for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
               "clip_sgd_step", "bn_batch_stats", "checkpoint", "cold_step"):

@@ -66,6 +66,23 @@ int main()
     if (h) CHECK(es_destroy(h) == ES_OK);
     CHECK(es_sync(nullptr) == ES_EINVAL && es_destroy(nullptr) == ES_EINVAL);
     CHECK(es_checkpoint_bytes(nullptr) == 0);
+    // the swap-in schedule: every fill waits for the reduce two buckets back, every reduce for its fill
+    for (uint32_t nbk : {0u, 1u, 2u, 3u, 37u, 1000u}) {
+        uint64_t n_ops = 0;
+        CHECK(es_plan_swap_in(nbk, nullptr, 0, &n_ops) == ES_OK && n_ops == 2ull * nbk);
+        std::vector<es_swap_op> ops(n_ops + 1);
+        CHECK(es_plan_swap_in(nbk, ops.data(), n_ops, &n_ops) == ES_OK);
+        for (uint64_t k = 0; k < n_ops; ++k) {
+            CHECK(ops[k].bucket == k / 2 && ops[k].half == (k / 2) % 2 && ops[k].kind == (k % 2 ? ES_SWAP_REDUCE : ES_SWAP_FILL));
+            CHECK(ops[k].wait == (k % 2 ? (int32_t)k - 1 : (k >= 4 ? (int32_t)k - 3 : -1)));
+        }
+        if (n_ops) CHECK(es_plan_swap_in(nbk, ops.data(), n_ops - 1, &n_ops) == ES_EINVAL);
+    }
+    // handle-free entry points reject bad sizes before any device work
+    CHECK(es_bn_workspace_floats(32, 64, 12544) == 64 * 98 && es_bn_workspace_floats(0, 1, 1) == 0);
+    CHECK(es_bn_workspace_floats(1ull << 20, 2, 1ull << 12) == 0);
+    CHECK(es_bn_batch_stats(nullptr, 2, 2, 8, nullptr, nullptr, nullptr, 0, nullptr) == ES_EINVAL);
+    CHECK(es_grad_sq_norm_static(nullptr, (1ull << 30) + 1, nullptr, nullptr) == ES_EINVAL);
     // scheduler-side planner: bit-set edges, clipped caps, ranking buffer of every size
     unsigned searched = 0;
     const double C[3] = {9.5, 4.25, 0.75};
