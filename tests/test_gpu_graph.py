@@ -20,7 +20,8 @@ def bits(a):
     return np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
 
 
-def test_captured_step_replays_bit_exactly():
+@pytest.mark.parametrize("flow", ["separate calls", "one launch per EST boundary"])
+def test_captured_step_replays_bit_exactly(flow):
     N, steps = 6, 4
     lay = buckets.custom([3 * 4096 + 37, 0, 3, 1001, 4 * N + 1, 40000], fan_in=9)
     sc = S.Scenario(N, lay, 4, 0x6A9, steps=steps, mask_n=517, bn_channels=(3, 64, 5))
@@ -44,7 +45,23 @@ def test_captured_step_replays_bit_exactly():
                 delta[e].copy_(S.bn_delta(sc, t, e, G.DEV))
             torch.cuda.synchronize()
 
+        def one_step_boundary():                          # what bench.py captures
+            for k, e in enumerate(sched):
+                prev = sched[k - 1] if k else None
+                nxt = sched[k + 1] if k + 1 < len(sched) else None
+                if nxt is not None and g.worker_of_est[nxt] != g.worker_of_est[e]:
+                    nxt = None
+                if prev is None or g.worker_of_est[prev] != g.worker_of_est[e]:
+                    job.ctx_restore(e)
+                job.dropout_mask(e, 0, masks[e], sc.p_drop)
+                G.bn_add_live(sc, job, e, delta[e])
+                B.check(B.es_est_boundary(job.h, e, nxt, all_b, [flat[e].data_ptr() + 4 * o for o, _ in lay.buckets]),
+                        "es_est_boundary", job.h)
+            job.reduce_sgd_step(sc.lr, sc.momentum)
+
         def one_step():
+            if flow != "separate calls":
+                return one_step_boundary()
             for k, e in enumerate(sched):
                 prev = sched[k - 1] if k else None
                 if prev is not None and g.worker_of_est[prev] == g.worker_of_est[e]:
