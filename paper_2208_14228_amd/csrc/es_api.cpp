@@ -389,12 +389,10 @@ int swap_prepare(es_handle* h)
 {
     if (h->swap_ready) return ES_OK;
     swap_release(h);
-    if (!h->s_swap) {
-        ES_HIP(h, hipStreamCreateWithFlags(&h->s_swap, hipStreamNonBlocking));
-        for (int k = 0; k < 2; ++k) {
-            ES_HIP(h, hipEventCreateWithFlags(&h->ev_filled[k], hipEventDisableTiming));
-            ES_HIP(h, hipEventCreateWithFlags(&h->ev_consumed[k], hipEventDisableTiming));
-        }
+    if (!h->s_swap) ES_HIP(h, hipStreamCreateWithFlags(&h->s_swap, hipStreamNonBlocking));
+    for (int k = 0; k < 2; ++k) {
+        if (!h->ev_filled[k]) ES_HIP(h, hipEventCreateWithFlags(&h->ev_filled[k], hipEventDisableTiming));
+        if (!h->ev_consumed[k]) ES_HIP(h, hipEventCreateWithFlags(&h->ev_consumed[k], hipEventDisableTiming));
     }
     const size_t nb = h->buckets.size();
     uint64_t lmax = 0;
@@ -1063,7 +1061,12 @@ static int reduce_common(es_handle* h, float* avg, float* p, float* v, float lr,
     bool any_on_host = false;
     for (const Worker& w : h->workers) any_on_host = any_on_host || w.grad_on_host;
     if (h->swap_in && any_on_host) {
-        int src = swap_reduce(h, avg, p, v, lr, mu);
+        int src;
+        try {
+            src = swap_reduce(h, avg, p, v, lr, mu);
+        } catch (const std::bad_alloc&) {
+            return ES_ENOMEM;
+        }
         if (src != ES_OK) return src;
         std::fill(h->accumulated.begin(), h->accumulated.end(), 0);
         h->n_accumulated = 0;
