@@ -846,3 +846,53 @@ def test_swap_in_of_host_resident_gradient_slots():
         S.assert_same(G.collect(sc3, job, {}), ref3, "in place under swap-in")
     finally:
         job.close()
+
+
+def test_random_flows_placements_and_occupancy_caps():
+    """Second seeded sweep, over the ways gradients reach the reduce: one launch per EST boundary,
+    several ESTs per staging launch, per-bucket calls; slots in HBM, in host memory read over the
+    link, or swapped in through the two buffers, or mixed by an HBM budget; any occupancy cap."""
+    rng = np.random.default_rng(20241127)
+    for case in range(24):
+        N = int(rng.choice([1, 2, 3, 5, 8, 11, 16, 20, 33]))
+        A = int(rng.choice([1, 4, 4, 32]))
+        lens = []
+        for _ in range(int(rng.integers(1, 7))):
+            kind = int(rng.integers(0, 4))
+            lens.append([int(rng.integers(0, 5)), int(rng.integers(1, 3 * N + 6)),
+                         2048 * N + int(rng.integers(-5, 6)), int(rng.integers(1, 90000))][kind])
+        sizes, left = [], N
+        while left:
+            k = int(rng.integers(1, left + 1))
+            sizes.append(k)
+            left -= k
+        g = (configs.contiguous, configs.round_robin)[int(rng.integers(0, 2))](sizes)
+        flow = ["boundary", "many", "per_bucket", "batched"][int(rng.integers(0, 4))]
+        placement = ["hbm", "host_direct", "host_swap", "mixed_swap"][int(rng.integers(0, 4))]
+        options = {"reduce_lds_pad_kib": int(rng.choice([-1, 0, 24, 64, 160])),
+                   "reduce_big_unroll": int(rng.choice([0, 8, 32])),
+                   "reduce_rank_batch": int(rng.choice([1, 4, 8]))}
+        fused = bool(rng.integers(0, 2))
+        streams = [True, "one"][int(rng.integers(0, 2))]
+        sc = S.Scenario(N, buckets.custom(lens, fan_in=3), A, 7000 + case, steps=2,
+                        mask_n=int(rng.integers(0, 200)), bn_channels=(int(rng.integers(1, 40)),))
+        what = (f"case {case}: N={N} A={A} lens={lens} grouping={g.name} flow={flow} placement={placement} "
+                f"{options} fused={fused} streams={streams}")
+        print("[gpu-case]", what, flush=True)
+        ref = S.run_ddp_reference(sc)
+        job = G.make_job(sc, configs.contiguous([N]), use_streams=streams, options=options)
+        try:
+            if placement != "hbm":
+                if placement == "mixed_swap":
+                    job.set_option("hbm_slot_budget_mib", 0 if len(sizes) == 1 else 1)
+                else:
+                    job.set_option("host_slots", 1)
+                job.set_option("swap_in", 0 if placement == "host_direct" else 1)
+            job.set_grouping(g.worker_of_est, g.slot_of_est)
+            G.init_contexts(sc, job)
+            masks = {}
+            G.run_steps(sc, job, g, fused=fused, masks=masks, boundary=(flow == "boundary"),
+                        many=(int(rng.integers(1, N + 1)) if flow == "many" else 0), batched=(flow == "batched"))
+            S.assert_same(G.collect(sc, job, masks), ref, what)
+        finally:
+            job.close()
