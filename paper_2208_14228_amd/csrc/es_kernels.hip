@@ -91,6 +91,22 @@ __device__ __forceinline__ void fold_batch(const float* const ES_CONST_AS* slots
     }
 }
 
+// The last N - k < 2*NBX ranks of a fold, in batches of NBX, NBX/2, .. 1 (same order of adds).
+template <int U, int NBX, int NT>
+__device__ __forceinline__ void fold_rest(const float* const ES_CONST_AS* slots, uint32_t N, uint32_t rank0,
+                                          uint32_t& k, const uint64_t (&e)[U], f4 (&acc)[U])
+{
+    if constexpr (NBX >= 1) {
+        if (k + NBX <= N) {
+            uint32_t r0 = rank0 + k;
+            if (r0 >= N) r0 -= N;
+            fold_batch<U, NBX, NT, false>(slots, N, r0, e, acc);
+            k += NBX;
+        }
+        fold_rest<U, NBX / 2, NT>(slots, N, rank0, k, e, acc);
+    }
+}
+
 template <bool SGD>
 __device__ __forceinline__ void finish_scalar(float acc, float fN, uint64_t e, float* avg,
                                               float* p, float* v, float lr, float mu)
@@ -156,7 +172,9 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
                 vv[u] = ld4_pv<(NT & 2) != 0>(v + e[u]);
             }
         }
-        // N = q*NB + rem ranks: q full batches, then the rest one rank at a time
+        // N = q*NB + rem ranks: q full batches, then the rest in batches of NB/2, NB/4, .. 1
+        // (a remainder taken one rank at a time leaves the wave with a single rank's loads in
+        // flight: measured -10 % at N = 12 when one workgroup has a CU to itself)
         uint32_t k;
         if (N >= (uint32_t)NB) {
             fold_batch<U, NB, NT, true>(slots, N, rank0, e, acc);
@@ -170,11 +188,7 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
             if (r0 >= N) r0 -= N;
             fold_batch<U, NB, NT, false>(slots, N, r0, e, acc);
         }
-        for (; k < N; ++k) {
-            uint32_t r0 = rank0 + k;
-            if (r0 >= N) r0 -= N;
-            fold_batch<U, 1, NT, false>(slots, N, r0, e, acc);
-        }
+        fold_rest<U, NB / 2, NT>(slots, N, rank0, k, e, acc);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             if (!ok[u]) continue;
