@@ -36,17 +36,22 @@ constexpr uint32_t kBlock = 256;
 constexpr uint32_t kReduceBlock = ES_REDUCE_BLOCK;   // lanes per workgroup of the ring-ordered reduce
 constexpr int kBigEpilogue = 16;                     // vectors per lane per pass of a big tile's update epilogue
 
-// Occupancy caps.  Measured on MI355X: the streaming kernels reach more of the HBM rate when a CU
-// has about 64-128 KiB of loads in flight than when it has several times that (more resident
-// workgroups = more DRAM regions open at once).  A launch reserves LDS it never touches so that
-// only 160 KiB / reserve workgroups fit a CU: 2 for the small-tile reduce (3 below 4 ranks, where
-// a workgroup has fewer loads in flight): +4-8 % at N = 2..10 on 26 M and 109 M parameters with
-// nothing cache-resident; 2 for the update and norm kernels: +4 % at 355 M parameters.
+// Occupancy caps.  Measured on MI355X: the streaming kernels reach more of the HBM rate with few
+// workgroups resident per CU (more resident workgroups = more DRAM regions open at once), as long
+// as each has a few tens of KiB of loads in flight.  A launch reserves LDS it never touches so that
+// only 160 KiB / reserve workgroups fit a CU.  Small-tile reduce: 2 per CU (3 below 4 ranks, where a
+// workgroup has fewer loads in flight): +4-8 % at N = 2..10 on 26 M and 109 M parameters with
+// nothing cache-resident; 1 per CU when every batch of the fold is full or nearly so (N = 8,
+// N >= 10) and parameters and momentum stream (another +3-7 %; with parameters and momentum coming
+// from the Infinity Cache one workgroup per CU is 7 % slower than two).  Update and norm kernels:
+// 2 per CU, +4 % at 355 M parameters.
 constexpr uint32_t kAuxLdsPad = 64u << 10;
-inline uint32_t reduce_lds_pad(int option_kib, uint32_t n_ranks)
+inline uint32_t reduce_lds_pad(int option_kib, uint32_t n_ranks, bool streaming_pv)
 {
     if (option_kib >= 0) return (uint32_t)option_kib << 10;
-    return (n_ranks < 4 ? 53u : 64u) << 10;
+    if (n_ranks < 4) return 53u << 10;
+    if (streaming_pv && (n_ranks == 8 || n_ranks >= 10)) return 160u << 10;
+    return 64u << 10;
 }
 constexpr uint32_t kCopyBlock = ES_COPY_BLOCK;   // lanes per workgroup of the batched staging copy
 
