@@ -430,7 +430,7 @@ int es_sync(es_handle* h);
  *                         per-EST gradients in host memory, section 3.2; here it is the
  *                         memory-pressure mode for N * n_params beyond HBM): staging and
  *                         reduce run unchanged and reach the gradients over the host link
- *   "hbm_slot_budget_mib" -1 (no limit, default) or >= 0: at the NEXT es_set_grouping the
+ *   "hbm_slot_budget_mib" -1 (no limit, default) or 0 .. 2^40: at the NEXT es_set_grouping the
  *                         workers' gradient arenas are placed in HBM in worker order until
  *                         this many MiB are used; the arenas that no longer fit spill to
  *                         pinned host memory (only what does not fit pays the host link)

@@ -561,11 +561,9 @@ int es_destroy(es_handle* h)
     dev_release(h, h->d_tiles);
     dev_release(h, (void*)h->d_slots);
     dev_release(h, h->d_partials);
+    if (h->s_swap) (void)hipStreamSynchronize(h->s_swap);
     swap_release(h);
-    if (h->s_swap) {
-        (void)hipStreamSynchronize(h->s_swap);
-        (void)hipStreamDestroy(h->s_swap);
-    }
+    if (h->s_swap) (void)hipStreamDestroy(h->s_swap);
     for (int k = 0; k < 2; ++k) {
         if (h->ev_filled[k]) (void)hipEventDestroy(h->ev_filled[k]);
         if (h->ev_consumed[k]) (void)hipEventDestroy(h->ev_consumed[k]);
@@ -1332,7 +1330,7 @@ try {
         return ES_OK;
     }
     if (k == "hbm_slot_budget_mib") {
-        if (value < -1) return ES_EINVAL;
+        if (value < -1 || value > (1ll << 40)) return ES_EINVAL;     // MiB: the byte count must fit 64 bits
         h->hbm_budget_mib = value;
         return ES_OK;
     }
