@@ -59,9 +59,10 @@ def parse():
                          "separate main/ctx/stage streams wired with events")
     ap.add_argument("--host-slots", action="store_true",
                     help="memory-pressure mode: gradient slots in pinned host memory (host-link bound)")
-    ap.add_argument("--overlap-demo", action="store_true",
-                    help="separate experiment: staging on its own stream overlapped with a compute-bound "
-                         "stand-in for the next EST's forward/backward (prints its own JSON line)")
+    ap.add_argument("--standin", type=int, default=0,
+                    help="side length of a bf16 matmul every EST runs on main before its boundary call: a "
+                         "compute-bound stand-in for forward/backward that staging on its own stream can "
+                         "overlap with (0 = none; the default line carries this experiment as staging_overlap)")
     ap.add_argument("--ceilings", action="store_true",
                     help="separate experiment: what this box's HBM gives the library's plain copy and "
                          "pure-read kernels on 1 GiB (prints its own JSON line)")
@@ -119,59 +120,6 @@ def est_switch_us(torch, reps=200):
         finally:
             job.close()
     return out
-
-
-def overlap_demo(a):
-    """Paper section 3.2: an EST's gradient copy is overlapped with the next EST's compute.
-    Each EST = one compute-bound stand-in (a bf16 matmul on main) followed by the staging of
-    its gradients; with one stream the two serialise, with a separate staging stream they
-    overlap.  Reports ms per global step for both."""
-    import torch
-
-    from paper_2208_14228_amd import binding as B
-    from paper_2208_14228_amd.job import ESTJob
-    from workloads import configs
-
-    cfg = configs.config(a.config)
-    lay, N, P = cfg.layout, cfg.n_logical, cfg.layout.n_params
-    dev = "cuda:0"
-    src = [torch.randn(P, device=dev) for _ in range(N)]
-    A = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
-    Bm = torch.randn(4096, 4096, device=dev, dtype=torch.bfloat16)
-    C = torch.empty(4096, 4096, device=dev, dtype=torch.bfloat16)
-    buckets = list(range(lay.n_buckets))
-    out = {"experiment": "staging overlapped with the next EST's compute", "config": a.config,
-           "n_logical": N, "n_params": P}
-    for mode in ("one", "two"):
-        job = ESTJob(N, P, lay.buckets, cfg.chunk_align, [], None, None, dev, use_streams=mode)
-        ptrs = [[src[e].data_ptr() + 4 * off for off, _ in lay.buckets] for e in range(N)]
-
-        def step(compute=True, stage=True):
-            for e in range(N):
-                if compute:
-                    with torch.cuda.stream(job.main):
-                        torch.mm(A, Bm, out=C)
-                if stage:
-                    B.es_accumulate_batch(job.h, e, buckets, ptrs[e])
-                else:
-                    B.es_accumulate_batch(job.h, e, buckets, [B.es_grad_slot(job.h, e, b) for b in buckets])
-            job.reduce_sgd_step(cfg.lr, cfg.momentum, store_avg=False)
-
-        def timed(**kw):
-            for _ in range(a.warmup):
-                step(**kw)
-            job.sync(); torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(a.steps):
-                step(**kw)
-            job.sync(); torch.cuda.synchronize()
-            return round((time.perf_counter() - t0) / a.steps * 1e3, 4)
-
-        out[f"streams_{mode}"] = {"compute_and_staging_ms": timed(),
-                                  "compute_only_ms": timed(stage=False),
-                                  "staging_only_ms": timed(compute=False)}
-        job.close()
-    print(json.dumps(out))
 
 
 def ceilings():
@@ -307,6 +255,12 @@ def measure(torch, a, cid, headline, oracle_leg):
         src.append(t)
     p0 = synth.params(lay, cfg.seed, dev)
     mask = torch.empty(32 * 128 * 768, dtype=torch.uint8, device=dev) if cfg.dropout else None
+    # optional compute-bound stand-in for an EST's forward+backward (a bf16 matmul on main): what the
+    # staging copy on its own stream can overlap with
+    standin = None
+    if getattr(a, "standin", 0):
+        standin = [torch.randn(a.standin, a.standin, device=dev, dtype=torch.bfloat16) for _ in range(2)]
+        standin.append(torch.empty(a.standin, a.standin, device=dev, dtype=torch.bfloat16))
     for e in range(N):
         if segs:
             job.ctx_save(e)
@@ -374,6 +328,9 @@ def measure(torch, a, cid, headline, oracle_leg):
             enter(e, one_launch)
             if mask is not None:
                 job.dropout_mask(e, 0, mask, configs.DROPOUT_P)
+            if standin is not None:
+                with torch.cuda.stream(job.main):
+                    torch.mm(standin[0], standin[1], out=standin[2])
             if one_launch:                    # stage e, save e, restore the worker's next EST: one launch
                 B.es_est_boundary_m(job.h, e, next_of.get(e), marshalled[e])
             elif a.per_bucket:
@@ -778,9 +735,6 @@ def main():
     if a.ceilings:
         print(json.dumps(ceilings()))
         return
-    if a.overlap_demo:
-        overlap_demo(a)
-        return
 
     import torch
 
@@ -802,15 +756,41 @@ def main():
     short = {c: measure(torch, a, c, False, oracle_leg) for c in others}
     # the same step of the context-heavy configuration with separate main / ctx / stage streams wired
     # by events (the save of a worker's last EST then overlaps the reduce): what the hand-offs cost
-    three = None
+    three = overlap = None
     if not a.no_extras and a.streams == "one" and not a.no_configs:
         import copy
-        a3 = copy.copy(a)
-        a3.streams, a3.no_cpu, a3.no_extras = "three", True, True
-        r3 = measure(torch, a3, 4, False, None)
+
+        def variant(streams, standin=0):
+            av = copy.copy(a)
+            av.streams, av.no_cpu, av.no_extras, av.standin = streams, True, True, standin
+            return measure(torch, av, 4, False, None)
+
+        r2, r3 = variant("two"), variant("three")
         three = {"note": "configuration 4 with separate main, ctx and stage streams (events between them) "
-                         "instead of one in-order stream", "ms_per_step": r3["ms_per_step"],
-                 "step_GBps": r3["step_GBps"], "one_stream_ms_per_step": short[4]["ms_per_step"] if 4 in short else None}
+                         "instead of one in-order stream; two_stream = main (also small state) + stage",
+                 "ms_per_step": r3["ms_per_step"], "step_GBps": r3["step_GBps"],
+                 "two_stream_ms_per_step": r2["ms_per_step"],
+                 "one_stream_ms_per_step": short[4]["ms_per_step"] if 4 in short else None}
+        # paper section 3.2: the gradient copy of an EST overlaps the next EST's compute.  Each EST
+        # computes a stand-in (one 4096^3 bf16 matmul on main) before its boundary call.
+        o1, o2, o3 = variant("one", 4096), variant("two", 4096), variant("three", 4096)
+        n_est = short[4]["n_logical"] if 4 in short else o1["n_logical"]
+        mm = [torch.randn(4096, 4096, device="cuda:0", dtype=torch.bfloat16) for _ in range(3)]
+        for _ in range(8):
+            torch.mm(mm[0], mm[1], out=mm[2])
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(4 * n_est):
+            torch.mm(mm[0], mm[1], out=mm[2])
+        torch.cuda.synchronize()
+        compute_ms = (time.perf_counter() - t0) / 4 * 1e3
+        del mm
+        overlap = {"note": "configuration 4, every EST runs a compute-bound stand-in (4096^3 bf16 matmul on main) "
+                           "before its boundary call: with a stage stream of its own the gradient copy "
+                           "overlaps the next EST's compute (paper section 3.2)",
+                   "standin_compute_ms_per_step": round(compute_ms, 4),
+                   "one_stream_ms_per_step": o1["ms_per_step"], "two_stream_ms_per_step": o2["ms_per_step"],
+                   "three_stream_ms_per_step": o3["ms_per_step"]}
     ceil = None if a.no_extras else ceilings()
     host_swap = None if a.no_extras else host_swap_leg(torch, a)
     head = measure(torch, a, a.config, True, oracle_leg)
@@ -853,6 +833,7 @@ def main():
         "ceilings": ceil,
         "host_swapped_slots": host_swap,
         "three_stream_step": three,
+        "staging_overlap": overlap,
     }
     for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
               "clip_sgd_step", "bn_batch_stats", "checkpoint", "cold_step"):

@@ -233,11 +233,12 @@ int es_accumulate_many(es_handle* h, uint32_t n_ests, const uint32_t* ests,
  * context is restored): es_accumulate_batch(est_out, ...) fused with
  * es_ctx_switch(est_out, est_in), or with es_ctx_save(est_out) if est_in is ES_NO_EST
  * (the last EST a worker runs in a global step).  Same results as the separate calls.
- * Runs on the stage stream, after the work already enqueued on main and on ctx; if est_in
- * is given, work enqueued on main afterwards waits for it (it needs the restored state), so
- * with separate streams this call does not overlap the copy with the next EST's compute:
- * callers who want that overlap use the separate calls.  est_out and est_in must be on the
- * same worker, whose live state must be bound if the layout has state segments.
+ * One launch when the stage stream IS the main stream (after the work already enqueued on
+ * main and on ctx).  When staging has a stream of its own the call keeps the overlap that
+ * stream is there for: the copy is enqueued on the stage stream and the save/restore on
+ * the ctx stream, as the separate calls would, and work enqueued on main afterwards waits
+ * for the restore only, not for the copy.  est_out and est_in must be on the same worker,
+ * whose live state must be bound if the layout has state segments.
  */
 #define ES_NO_EST 0xFFFFFFFFu
 int es_est_boundary(es_handle* h, uint32_t est_out, uint32_t est_in, uint32_t n,

@@ -962,6 +962,25 @@ try {
     RunBuilder rb;
     collect_runs(h, est_out, n, buckets, d_grad_buckets, rb);
     const uint32_t n_pieces = h->seg_bytes.empty() ? 0 : w.n_pieces;
+    if (h->s_stage != h->s_main) {
+        // Staging has a stream of its own so that the copy overlaps the next EST's compute: one
+        // fused launch would make main wait for the whole copy.  The copy goes to the stage
+        // stream and the small-state switch where es_ctx_switch puts it; main waits for the
+        // switch alone.
+        if (!rb.launches.empty()) {
+            if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;
+            if ((rc = enqueue_staging(h, rb, dma_staging(h, est_out))) != ES_OK) return rc;
+            h->stage_pending = true;
+        }
+        mark_batch(h, est_out, n, buckets);
+        if (n_pieces) {
+            if ((rc = order_after(h, h->s_ctx, h->s_main, h->ev_main)) != ES_OK) return rc;
+            ES_HIP(h, launch_ctx(h->s_ctx, w.d_pieces, n_pieces, ctx_base(h, est_out),
+                                 has_in ? ctx_base(h, est_in) : nullptr, has_in ? kSwitch : kSave));
+            if (has_in && (rc = order_after(h, h->s_main, h->s_ctx, h->ev_ctx)) != ES_OK) return rc;
+        }
+        return ES_OK;
+    }
     if (n_pieces || !rb.launches.empty()) {
         // after the outgoing EST's compute on main and after earlier context traffic on the ctx stream
         if ((rc = order_after(h, h->s_stage, h->s_main, h->ev_main)) != ES_OK) return rc;

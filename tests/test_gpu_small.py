@@ -662,13 +662,14 @@ def test_staging_from_sources_off_a_16_byte_boundary():
 
 def test_est_boundary_in_one_launch_matches_the_separate_calls():
     """es_est_boundary = staging of the outgoing EST + save + restore of the next EST of its worker in
-    one kernel launch: same bits as the reference for every grouping, on one stream and on three."""
+    one kernel launch on one stream; with a stage stream of its own (two or three streams) the copy goes
+    there and the switch to the ctx stream.  Same bits as the reference for every grouping."""
     N = 8
     sc = ragged_scenario(N, 4, 91, steps=3, mask_n=517, bn_channels=(64, 3, 128, 2048))
     ref = S.run_ddp_reference(sc)
     for g in (configs.contiguous([8]), configs.contiguous([3, 5]), configs.round_robin([2, 6]),
               configs.contiguous([1] * 8, "1x8")):
-        for streams in ("one", True):
+        for streams in ("one", "two", True):
             got = G.run_gpu(sc, g, fused=True, boundary=True, use_streams=streams)
             S.assert_same(got, ref, f"boundary {g.name} streams={streams}")
     # a layout without small state: the boundary is the staging copy alone
