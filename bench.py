@@ -461,6 +461,37 @@ def measure(torch, a, cid, headline, oracle_leg):
                     "at this size, streaming_pv = option nontemporal_pv=1", **cold}
         del sweep
 
+    # ---- the two halves as kernels of their own: the reduce alone ((N+1)*4P bytes: N gradient
+    # sets read, the average written) and the update alone (5*4P bytes) ----
+    if fused and not a.no_extras and not a.host_slots:
+        n_split = min(steps, 10)
+        ev_a, ev_b = events(n_split), events(n_split)
+        for i in range(-2, n_split):
+            for e in sched:                                       # gradients stay where they are in the slots
+                B.es_accumulate_batch_m(job.h, e, slot_m[e])
+            if i >= 0:
+                ev_a[i][0].record(job.main)
+            job.ring_order_reduce()
+            if i >= 0:
+                ev_a[i][1].record(job.main)
+                ev_b[i][0].record(job.main)
+            job.sgd_step(cfg.lr, cfg.momentum)
+            if i >= 0:
+                ev_b[i][1].record(job.main)
+        job.sync(); torch.cuda.synchronize()
+        ms_a = [x.elapsed_time(y) for x, y in ev_a]
+        ms_b = [x.elapsed_time(y) for x, y in ev_b]
+        gb_a = (N + 1) * 4 * P / (statistics.fmean(ms_a) * 1e-3) / 1e9
+        gb_b = 5 * 4 * P / (statistics.fmean(ms_b) * 1e-3) / 1e9
+        res["reduce_alone"] = {"kernel": kname.replace(" (fused SGD)", ""), "bytes_per_launch": (N + 1) * 4 * P,
+                               "launch_ms": stats_ms(ms_a), "achieved": round(gb_a, 1), "unit": "GB/s",
+                               "frac": round(gb_a / HBM_PEAK_GBPS, 4)}
+        res["sgd_alone"] = {"kernel": "k_sgd", "bytes_per_launch": 5 * 4 * P, "launch_ms": stats_ms(ms_b),
+                            "achieved": round(gb_b, 1), "unit": "GB/s", "frac": round(gb_b / HBM_PEAK_GBPS, 4),
+                            "memory": ("the averaged gradient the reduce has just written, parameters and momentum "
+                                       "can come from the Infinity Cache at this size" if 3 * 4 * P <= CACHE_FIT_BYTES
+                                       else "streams from and to HBM")}
+
     if not a.no_extras:
         def timed_wall(fn):
             for _ in range(warmup):
@@ -835,13 +866,13 @@ def main():
         "three_stream_step": three,
         "staging_overlap": overlap,
     }
-    for k in ("sgd", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
+    for k in ("sgd", "reduce_alone", "sgd_alone", "reduce_hbm_only", "staged_16_per_launch_step", "in_place_last_step", "graph_step", "zero_copy_step", "grad_sq_norm",
               "clip_sgd_step", "bn_batch_stats", "checkpoint", "cold_step"):
         if k in head:
             out[k] = head[k]
     if not a.no_configs:
         keep = ("config", "workload", "ms_per_step", "step_GBps", "step_frac", "step_bytes", "reduce", "staging",
-                "reduce_hbm_only", "cold_step", "staged_16_per_launch_step", "in_place_last_step", "graph_step",
+                "reduce_alone", "sgd_alone", "reduce_hbm_only", "cold_step", "staged_16_per_launch_step", "in_place_last_step", "graph_step",
                 "zero_copy_step", "context_bytes_per_est", "mask_bytes_per_est", "zero_ulp",
                 "cpu_baseline", "cpu_baseline_all_cores")
         allc = dict(short)

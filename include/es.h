@@ -455,8 +455,10 @@ int es_sync(es_handle* h);
  *                         (160 KiB per CU); -1 = 64 (2 per CU), 53 (3 per CU) below 4 ranks, 160
  *                         (1 per CU) for 8 or at least 10 ranks when parameters and momentum stream
  *   "nontemporal"         0/1: streaming hint on gradient loads
- *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the fused
- *                         update (default: 1 if both vectors together exceed 284 MiB, else 0)
+ *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the update
+ *                         (fused or es_sgd_step / es_clip_sgd_step) and on the store of the
+ *                         averaged gradient (default: 1 if parameters and momentum together
+ *                         exceed 284 MiB, else 0)
  *   "reduce_big_unroll"   0, 8, 16 or 32: if not 0, full aligned stretches of a ring chunk
  *                         are handled in big tiles of 256 * value * 4 elements (long
  *                         contiguous reads per gradient stream; default 32 from

@@ -1129,7 +1129,7 @@ int es_sgd_step(es_handle* h, float* d_param, float* d_momentum, const float* d_
     if (overlap(d_param, d_momentum, vec_bytes) || overlap(d_param, d_avg_grad, vec_bytes) ||
         overlap(d_momentum, d_avg_grad, vec_bytes))
         return ES_EINVAL;
-    ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu));
+    ES_HIP(h, launch_sgd(h->s_main, d_param, d_momentum, d_avg_grad, h->P, lr, mu, h->shape.nontemporal_pv != 0));
     return ES_OK;
 }
 
@@ -1154,7 +1154,8 @@ int es_clip_sgd_step(es_handle* h, float* d_param, float* d_momentum, const floa
     if (overlap(d_param, d_momentum, vec_bytes) || overlap(d_param, d_avg_grad, vec_bytes) ||
         overlap(d_momentum, d_avg_grad, vec_bytes))
         return ES_EINVAL;
-    ES_HIP(h, launch_sgd_clip(h->s_main, d_param, d_momentum, d_avg_grad, h->P, d_norm2, max_norm, eps, lr, mu));
+    ES_HIP(h, launch_sgd_clip(h->s_main, d_param, d_momentum, d_avg_grad, h->P, d_norm2, max_norm, eps, lr, mu,
+                              h->shape.nontemporal_pv != 0));
     return ES_OK;
 }
 

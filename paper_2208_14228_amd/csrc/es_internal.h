@@ -72,7 +72,8 @@ struct ReduceShape {
     int nontemporal;   // streaming hint on gradient loads
     int big_unroll;    // 0, or vectors per lane of a big tile (8, 16, 32): see k_ring_reduce_big
     int big_rank_batch;
-    int nontemporal_pv; // streaming hint on parameter / momentum traffic of the fused update
+    int nontemporal_pv; // streaming hint on parameter / momentum traffic of the update and on the store of the
+                        // averaged gradient
     int lds_pad_kib = -1; // KiB of LDS reserved (and never touched) per workgroup of the small-tile kernel, to cap the
                           // workgroups resident per CU; -1 = default for the rank count (see reduce_lds_pad)
 };
@@ -88,8 +89,9 @@ hipError_t launch_ring_reduce(hipStream_t s, const Tile* tiles, uint32_t n_tiles
                               float* avg, float* p, float* v, float lr, float mu,
                               ReduceShape shape);
 
+// stream_pv: streaming accesses to p and v (vectors too large to stay in the caches between steps)
 hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
-                      float lr, float mu);
+                      float lr, float mu, bool stream_pv);
 
 // dst[0..n) <- src[0..n) floats (any 4-byte alignment)
 hipError_t launch_copy_f32(hipStream_t s, float* dst, const float* src, uint64_t n);
@@ -133,7 +135,7 @@ hipError_t launch_sq_norm_static(hipStream_t s, const float* x, uint64_t n, floa
 
 // v <- mu*v + coef*g ; p <- p - lr*v with coef = min(1, max_norm / (norm2[1] + eps)) formed on the device
 hipError_t launch_sgd_clip(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
-                           const float* norm2, float max_norm, float eps, float lr, float mu);
+                           const float* norm2, float max_norm, float eps, float lr, float mu, bool stream_pv);
 
 // Per-channel mean and biased variance of x[B][C][HW] along the fixed tree; B * HW < 2^31,
 // C <= 65535; part: scratch of C * ceil(B * HW / 4096) floats

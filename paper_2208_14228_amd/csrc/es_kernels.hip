@@ -34,10 +34,14 @@ __device__ __forceinline__ f4 ld4(const float* p)
 
 __device__ __forceinline__ void st4(float* p, f4 x) { *reinterpret_cast<f4*>(p) = x; }
 
-// Parameter / momentum traffic of the fused update.  Touched once per global
-// step: when both vectors fit in the 256 MB Infinity Cache they are left cacheable
-// and come back from it in the next step (measured +13 % at P = 25.6 M);
-// when they do not, streaming accesses are faster (+6 % at P = 109 M).
+// Parameter / momentum traffic of the update, and the store of the averaged
+// gradient.  Touched once per global step: when the vectors fit in the 256 MB
+// Infinity Cache they are left cacheable and come back from it (parameters and
+// momentum in the next step, measured +13 % at P = 25.6 M; the averaged gradient
+// in the update kernel that follows an unfused reduce); when they do not,
+// streaming accesses are faster (fused: +6 % at P = 109 M; the unfused reduce:
+// +11 % at P = 109 M, N = 16 and +13 % at P = 355 M, N = 64 from the store of the
+// averaged gradient alone).
 template <bool NTPV>
 __device__ __forceinline__ f4 ld4_pv(const float* p)
 {
@@ -193,7 +197,7 @@ __device__ __forceinline__ void small_tile(const float* const ES_CONST_AS* slots
         for (int u = 0; u < U; ++u) {
             if (!ok[u]) continue;
             const f4 a = acc[u] / fN;
-            if (avg) st4(avg + e[u], a);
+            if (avg) st4_pv<(NT & 2) != 0>(avg + e[u], a);
             if constexpr (SGD) {
                 const f4 mv = mu * vv[u];
                 const f4 vn = mv + a;
@@ -315,7 +319,7 @@ __global__ __launch_bounds__(kReduceBlock) void k_ring_reduce_big(const Tile* ti
         for (int q = 0; q < EG; ++q) {
             const uint64_t e = e0 + 256 * (u0 + q);
             const f4 a = acc[u0 + q] / fN;
-            if (avg) st4(avg + e, a);
+            if (avg) st4_pv<(NT & 2) != 0>(avg + e, a);
             if constexpr (SGD) {
                 const f4 mv = mu * vv[q];
                 const f4 vn = mv + a;
@@ -338,7 +342,12 @@ static hipError_t launch_reduce_unb(hipStream_t s, const Tile* tiles, uint32_t n
 #define ES_LAUNCH(NTV, SGDV) \
     hipLaunchKernelGGL((k_ring_reduce<U, NB, NTV, SGDV>), grid, block, lds_pad, s, tiles, slots, N, avg, p, v, lr, mu)
     if (!sgd) {
-        if (nt & 1) ES_LAUNCH(1, false); else ES_LAUNCH(0, false);
+        switch (nt & 3) {
+        case 0: ES_LAUNCH(0, false); break;
+        case 1: ES_LAUNCH(1, false); break;
+        case 2: ES_LAUNCH(2, false); break;
+        default: ES_LAUNCH(3, false); break;
+        }
     } else {
         switch (nt & 3) {
         case 0: ES_LAUNCH(0, true); break;
@@ -377,7 +386,12 @@ static hipError_t launch_reduce_big(hipStream_t s, const Tile* tiles, uint32_t n
 #define ES_LAUNCH(NTV, SGDV) \
     hipLaunchKernelGGL((k_ring_reduce_big<UB, NBB, NTV, SGDV>), grid, block, 0, s, tiles, n_big, slots, N, avg, p, v, lr, mu)
     if (!sgd) {
-        if (nt & 1) ES_LAUNCH(1, false); else ES_LAUNCH(0, false);
+        switch (nt & 3) {
+        case 0: ES_LAUNCH(0, false); break;
+        case 1: ES_LAUNCH(1, false); break;
+        case 2: ES_LAUNCH(2, false); break;
+        default: ES_LAUNCH(3, false); break;
+        }
     } else {
         switch (nt & 3) {
         case 0: ES_LAUNCH(0, true); break;
@@ -449,6 +463,7 @@ hipError_t launch_patch_slots(hipStream_t s, const float** table, const InPlace&
 // ---------------------------------------------------------------------------
 constexpr int kSgdU = 4;
 
+template <bool NTPV>
 __global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ p, float* __restrict__ v,
                                                 const float* __restrict__ g, uint64_t n,
                                                 float lr, float mu)
@@ -461,8 +476,8 @@ __global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ p, float* __
         const uint64_t i = base + (uint64_t)u * kBlock;
         if (i < nvec) {
             gg[u] = ld4<true>(g + 4 * i);
-            pp[u] = ld4<false>(p + 4 * i);
-            vv[u] = ld4<false>(v + 4 * i);
+            pp[u] = ld4_pv<NTPV>(p + 4 * i);
+            vv[u] = ld4_pv<NTPV>(v + 4 * i);
         }
     }
 #pragma unroll
@@ -472,8 +487,8 @@ __global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ p, float* __
             const f4 mv = mu * vv[u];
             const f4 vn = mv + gg[u];
             const f4 st = lr * vn;
-            st4(v + 4 * i, vn);
-            st4(p + 4 * i, pp[u] - st);
+            st4_pv<NTPV>(v + 4 * i, vn);
+            st4_pv<NTPV>(p + 4 * i, pp[u] - st);
         }
     }
     if (blockIdx.x == 0) {
@@ -489,13 +504,16 @@ __global__ __launch_bounds__(kBlock) void k_sgd(float* __restrict__ p, float* __
 }
 
 hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_t n, float lr,
-                      float mu)
+                      float mu, bool stream_pv)
 {
     if (n == 0) return hipSuccess;
     const uint64_t nvec = n >> 2;
     uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
     if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(k_sgd, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, lr, mu);
+    if (stream_pv)
+        hipLaunchKernelGGL(k_sgd<true>, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, lr, mu);
+    else
+        hipLaunchKernelGGL(k_sgd<false>, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, lr, mu);
     return hipGetLastError();
 }
 
@@ -503,6 +521,7 @@ hipError_t launch_sgd(hipStream_t s, float* p, float* v, const float* g, uint64_
 //     coef = min(1, max_norm / (norm + eps))
 // from the norm es_grad_sq_norm left in device memory (no host round trip) and scales its
 // gradient elements by it; coef * g is rounded on its own before it enters the momentum.
+template <bool NTPV>
 __global__ __launch_bounds__(kBlock) void k_sgd_clip(float* __restrict__ p, float* __restrict__ v,
                                                      const float* __restrict__ g, uint64_t n,
                                                      const float* __restrict__ norm2, float max_norm,
@@ -519,8 +538,8 @@ __global__ __launch_bounds__(kBlock) void k_sgd_clip(float* __restrict__ p, floa
         const uint64_t i = base + (uint64_t)u * kBlock;
         if (i < nvec) {
             gg[u] = ld4<true>(g + 4 * i);
-            pp[u] = ld4<false>(p + 4 * i);
-            vv[u] = ld4<false>(v + 4 * i);
+            pp[u] = ld4_pv<NTPV>(p + 4 * i);
+            vv[u] = ld4_pv<NTPV>(v + 4 * i);
         }
     }
 #pragma unroll
@@ -531,8 +550,8 @@ __global__ __launch_bounds__(kBlock) void k_sgd_clip(float* __restrict__ p, floa
             const f4 mv = mu * vv[u];
             const f4 vn = mv + gs;
             const f4 st = lr * vn;
-            st4(v + 4 * i, vn);
-            st4(p + 4 * i, pp[u] - st);
+            st4_pv<NTPV>(v + 4 * i, vn);
+            st4_pv<NTPV>(p + 4 * i, pp[u] - st);
         }
     }
     if (blockIdx.x == 0) {
@@ -549,14 +568,18 @@ __global__ __launch_bounds__(kBlock) void k_sgd_clip(float* __restrict__ p, floa
 }
 
 hipError_t launch_sgd_clip(hipStream_t s, float* p, float* v, const float* g, uint64_t n,
-                           const float* norm2, float max_norm, float eps, float lr, float mu)
+                           const float* norm2, float max_norm, float eps, float lr, float mu, bool stream_pv)
 {
     if (n == 0) return hipSuccess;
     const uint64_t nvec = n >> 2;
     uint64_t blocks = (nvec + kBlock * kSgdU - 1) / (kBlock * kSgdU);
     if (blocks == 0) blocks = 1;
-    hipLaunchKernelGGL(k_sgd_clip, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, norm2, max_norm,
-                       eps, lr, mu);
+    if (stream_pv)
+        hipLaunchKernelGGL(k_sgd_clip<true>, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, norm2,
+                           max_norm, eps, lr, mu);
+    else
+        hipLaunchKernelGGL(k_sgd_clip<false>, dim3((uint32_t)blocks), dim3(kBlock), kAuxLdsPad, s, p, v, g, n, norm2,
+                           max_norm, eps, lr, mu);
     return hipGetLastError();
 }
 

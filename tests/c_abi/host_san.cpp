@@ -12,13 +12,13 @@
 namespace es {
 hipError_t launch_ring_reduce(hipStream_t, const Tile*, uint32_t, uint32_t, const float* const*, uint32_t,
                               float*, float*, float*, float, float, ReduceShape) { return hipSuccess; }
-hipError_t launch_sgd(hipStream_t, float*, float*, const float*, uint64_t, float, float) { return hipSuccess; }
+hipError_t launch_sgd(hipStream_t, float*, float*, const float*, uint64_t, float, float, bool) { return hipSuccess; }
 hipError_t launch_copy_f32(hipStream_t, float*, const float*, uint64_t) { return hipSuccess; }
 hipError_t launch_copy_runs(hipStream_t, const CopyRuns&) { return hipSuccess; }
 hipError_t launch_patch_slots(hipStream_t, const float**, const InPlace&) { return hipSuccess; }
 hipError_t launch_ctx(hipStream_t, const Piece*, uint32_t, uint8_t*, const uint8_t*, CtxDir) { return hipSuccess; }
 hipError_t launch_est_boundary(hipStream_t, const CopyRuns&, const Piece*, uint32_t, uint8_t*, const uint8_t*, CtxDir) { return hipSuccess; }
-hipError_t launch_sgd_clip(hipStream_t, float*, float*, const float*, uint64_t, const float*, float, float, float, float) { return hipSuccess; }
+hipError_t launch_sgd_clip(hipStream_t, float*, float*, const float*, uint64_t, const float*, float, float, float, float, bool) { return hipSuccess; }
 hipError_t launch_bn_batch_stats(hipStream_t, const float*, uint32_t, uint32_t, uint32_t, float*, float*, float*) { return hipSuccess; }
 hipError_t launch_copy_bytes(hipStream_t, uint8_t*, const uint8_t*, uint64_t) { return hipSuccess; }
 hipError_t launch_sq_norm(hipStream_t, const float*, uint64_t, float*, float*) { return hipSuccess; }
