@@ -78,7 +78,7 @@ def test_bn_witnesses_and_arguments():
 def test_clipped_update_parity():
     rng = np.random.default_rng(9)
     n = 3 * 4096 + 37
-    for max_norm, eps in ((0.5, 1e-6), (1e9, 1e-6), (2.0, 0.0)):
+    for max_norm, eps, streaming in ((0.5, 1e-6, 0), (1e9, 1e-6, 1), (2.0, 0.0, 1), (0.5, 1e-6, 1)):
         g = rng.standard_normal(n).astype(np.float32) * np.float32(0.05)
         p0 = rng.standard_normal(n).astype(np.float32)
         v0 = rng.standard_normal(n).astype(np.float32)
@@ -89,6 +89,7 @@ def test_clipped_update_parity():
         oracle.sgd_momentum_scaled(want_p, want_v, g, 0.1, 0.9, coef)
         job = ESTJob(1, n, [(0, n)], 1)
         try:
+            job.set_option("nontemporal_pv", streaming)      # cacheable and streaming form of the update kernel
             job.p.copy_(torch.from_numpy(p0)); job.v.copy_(torch.from_numpy(v0)); job.avg.copy_(torch.from_numpy(g))
             out2 = torch.zeros(2, device=DEV)
             torch.cuda.synchronize()
