@@ -874,7 +874,7 @@ def test_random_flows_placements_and_occupancy_caps():
                    "reduce_big_unroll": int(rng.choice([0, 8, 32])),
                    "reduce_rank_batch": int(rng.choice([1, 4, 8]))}
         fused = bool(rng.integers(0, 2))
-        streams = [True, "one"][int(rng.integers(0, 2))]
+        streams = [True, "one", "two"][int(rng.integers(0, 3))]
         sc = S.Scenario(N, buckets.custom(lens, fan_in=3), A, 7000 + case, steps=2,
                         mask_n=int(rng.integers(0, 200)), bn_channels=(int(rng.integers(1, 40)),))
         what = (f"case {case}: N={N} A={A} lens={lens} grouping={g.name} flow={flow} placement={placement} "
