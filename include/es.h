@@ -452,7 +452,8 @@ int es_sync(es_handle* h);
  *                         default 8, or the largest power of two <= n_logical below that)
  *   "reduce_lds_pad_kib"  -1 (default) or 0 .. 160: KiB of LDS a workgroup of the small-tile reduce
  *                         reserves without using it, which caps the workgroups resident per CU
- *                         (160 KiB per CU); -1 = 64 (2 per CU), 53 (3 per CU) below 4 ranks, 160
+ *                         (160 KiB per CU); -1 = 64 (2 per CU), below 4 ranks 53 (3 per CU; 32 = 5 per CU
+ *                         for the unfused reduce), 160
  *                         (1 per CU) for 8 or at least 10 ranks when parameters and momentum stream
  *   "nontemporal"         0/1: streaming hint on gradient loads
  *   "nontemporal_pv"      0/1: streaming hint on parameter and momentum traffic of the update

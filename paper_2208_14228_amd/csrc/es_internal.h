@@ -46,10 +46,12 @@ constexpr int kBigEpilogue = 16;                     // vectors per lane per pas
 // from the Infinity Cache one workgroup per CU is 7 % slower than two).  Update and norm kernels:
 // 2 per CU, +4 % at 355 M parameters.
 constexpr uint32_t kAuxLdsPad = 64u << 10;
-inline uint32_t reduce_lds_pad(int option_kib, uint32_t n_ranks, bool streaming_pv)
+inline uint32_t reduce_lds_pad(int option_kib, uint32_t n_ranks, bool streaming_pv, bool fused)
 {
     if (option_kib >= 0) return (uint32_t)option_kib << 10;
-    if (n_ranks < 4) return 53u << 10;
+    // below 4 ranks the unfused reduce is close to a copy and wants more waves still (5 per CU:
+    // 57 -> 77 % of the HBM peak at N = 1, 70 -> 80 % at N = 3 on 109 M parameters)
+    if (n_ranks < 4) return fused ? 53u << 10 : 32u << 10;
     if (streaming_pv && (n_ranks == 8 || n_ranks >= 10)) return 160u << 10;
     return 64u << 10;
 }

@@ -367,11 +367,11 @@ static hipError_t launch_reduce_u(hipStream_t s, const Tile* tiles, uint32_t n_t
 {
     const int nt = (sh.nontemporal ? 1 : 0) | (sh.nontemporal_pv ? 2 : 0);
     switch (sh.rank_batch) {
-    case 1:  return launch_reduce_unb<U, 1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr));
-    case 2:  return launch_reduce_unb<U, 2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr));
-    case 4:  return launch_reduce_unb<U, 4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr));
-    case 8:  return launch_reduce_unb<U, 8>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr));
-    case 16: return launch_reduce_unb<U, 16>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr));
+    case 1:  return launch_reduce_unb<U, 1>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr, p != nullptr));
+    case 2:  return launch_reduce_unb<U, 2>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr, p != nullptr));
+    case 4:  return launch_reduce_unb<U, 4>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr, p != nullptr));
+    case 8:  return launch_reduce_unb<U, 8>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr, p != nullptr));
+    case 16: return launch_reduce_unb<U, 16>(s, tiles, n_tiles, slots, N, avg, p, v, lr, mu, nt, reduce_lds_pad(sh.lds_pad_kib, N, sh.nontemporal_pv != 0 && p != nullptr, p != nullptr));
     default: return hipErrorInvalidValue;
     }
 }
