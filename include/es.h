@@ -237,7 +237,9 @@ int es_accumulate_many(es_handle* h, uint32_t n_ests, const uint32_t* ests,
  * main and on ctx).  When staging has a stream of its own the call keeps the overlap that
  * stream is there for: the copy is enqueued on the stage stream and the save/restore on
  * the ctx stream, as the separate calls would, and work enqueued on main afterwards waits
- * for the restore only, not for the copy.  est_out and est_in must be on the same worker,
+ * for the restore only, not for the copy (so, as for es_accumulate, the sources must stay
+ * unmodified until the copy has run: es_stage_fence orders main after it).  est_out and est_in
+ * must be on the same worker,
  * whose live state must be bound if the layout has state segments.
  */
 #define ES_NO_EST 0xFFFFFFFFu
