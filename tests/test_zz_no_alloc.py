@@ -71,3 +71,21 @@ def test_limits_and_arguments():
     B.check(B.es_grad_sq_norm_static(x.data_ptr(), 8, out.data_ptr(), 0), "es_grad_sq_norm_static")
     torch.cuda.synchronize()
     assert out.cpu().numpy()[0] == 8.0
+
+
+def test_maximum_size():
+    """n = 2^30, the documented limit: every one of the 2^18 partials of the fixed array is used."""
+    n = 1 << 30
+    rng = np.random.default_rng(5)
+    x = rng.integers(-8, 9, n, dtype=np.int8).astype(np.float32)
+    x *= np.float32(1.0 / 3.0)                           # squares no longer exact: the order matters
+    want = np.float32(oracle.tree_sumsq(x))
+    d = torch.from_numpy(x).to(DEV)
+    out = torch.full((2,), float("nan"), device=DEV)
+    torch.cuda.synchronize()
+    print(f"[gpu-case] es_grad_sq_norm_static n={n}", flush=True)
+    B.check(B.es_grad_sq_norm_static(d.data_ptr(), n, out.data_ptr(), 0), "es_grad_sq_norm_static")
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert got[0].view(np.uint32) == want.view(np.uint32), (got, want)
+    assert got[1].view(np.uint32) == np.sqrt(want).view(np.uint32)
