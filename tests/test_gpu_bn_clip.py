@@ -39,7 +39,8 @@ def gpu_bn(x: np.ndarray, shift=0, stream=None):
 
 
 @pytest.mark.parametrize("Bn,C,HW", [(1, 1, 1), (2, 3, 49), (3, 2, 4097), (5, 4, 3136), (32, 7, 196),
-                                     (7, 1, 150_001), (4, 64, 56 * 56), (2, 300, 13)])
+                                     (7, 1, 150_001), (4, 64, 56 * 56), (2, 300, 13),
+                                     (1, 65535, 5), (2, 1, (1 << 26) + 3)])    # most channels; a long channel
 def test_bn_statistics_parity(Bn, C, HW):
     rng = np.random.default_rng(Bn * 1000 + HW)
     x = (rng.standard_normal((Bn, C, HW)) * 3 + rng.standard_normal((1, C, 1)) * 10).astype(np.float32)
