@@ -57,3 +57,19 @@ def fold_reduce(rank_grads: np.ndarray, A: int = 1) -> np.ndarray:
     N, L = rank_grads.shape
     g = np.asarray(rank_grads, dtype=np.float32)
     return fold_window(lambda r, a, b: g[r, a:b], 0, L, L, N, A)
+
+
+def fold_reduce_gather(rank_grads: np.ndarray, A: int = 1) -> np.ndarray:
+    """The same closed form, one gather per step of the fold instead of one loop per chunk:
+    element i of chunk c(i) adds ranks c(i), c(i)+1, ... (mod N) in turn.  For buckets with very
+    many ranks and few elements per chunk, where the per-chunk loop above is too slow."""
+    g = np.asarray(rank_grads, dtype=np.float32)
+    N, L = g.shape
+    if L == 0:
+        return np.zeros(0, dtype=np.float32)
+    idx = np.arange(L)
+    start = idx // chunk_len(L, N, A)
+    acc = g[start % N, idx].astype(np.float32, copy=True)
+    for k in range(1, N):
+        acc = acc + g[(start + k) % N, idx]
+    return acc / np.float32(N)

@@ -121,10 +121,19 @@ def test_matches_closed_form_fold():
                 g = wide_random((N, L), 1000 * N + 10 * L + A)
                 assert np.array_equal(bits(oracle.ring_order_reduce(g, A=A)),
                                       bits(fold_def.fold_reduce(g, A=A))), (N, A, L)
+                assert np.array_equal(bits(oracle.ring_order_reduce(g, A=A)),
+                                      bits(fold_def.fold_reduce_gather(g, A=A))), (N, A, L)
     for N, L, A in ((16, 5003, 4), (64, 3001, 4), (7, 1 << 14, 1)):
         g = wide_random((N, L), N + L)
         assert np.array_equal(bits(oracle.ring_order_reduce(g, A=A)),
                               bits(fold_def.fold_reduce(g, A=A)))
+        assert np.array_equal(bits(oracle.ring_order_reduce(g, A=A)),
+                              bits(fold_def.fold_reduce_gather(g, A=A)))
+    # many more ranks than elements: most chunks empty, start ranks far apart
+    for N, L, A in ((300, 7, 1), (300, 41, 4), (1000, 1003, 1)):
+        g = wide_random((N, L), N + L)
+        assert np.array_equal(bits(oracle.ring_order_reduce(g, A=A)),
+                              bits(fold_def.fold_reduce_gather(g, A=A)))
 
 
 def _read_witness():
