@@ -902,3 +902,51 @@ def test_random_flows_placements_and_occupancy_caps():
             S.assert_same(G.collect(sc, job, masks), ref, what)
         finally:
             job.close()
+
+
+def test_large_and_odd_state_segments_through_every_context_path():
+    """Context traffic as plain bytes: segments of 3 MiB + 5, 7, 16 and 12 KiB + 4 bytes, live tensors
+    16-byte aligned, 4-byte aligned and at odd addresses; save, restore, the fused switch and the
+    one-launch EST boundary all have to move exactly the segment's bytes."""
+    segs = [(3 << 20) + 5, 7, 16, 12 * 1024 + 4]
+    rng = np.random.default_rng(31)
+    for shift in (0, 4, 1):
+        def alloc(nb, shift=shift):
+            base = torch.full((nb + 64,), 0xEE, dtype=torch.uint8, device=G.DEV)
+            return base[shift:shift + nb]
+        job = ESTJob(3, 64, [(0, 64)], 4, segs, [0, 0, 0], [2, 0, 1], live_alloc=alloc)
+        try:
+            pat = [[torch.from_numpy(rng.integers(0, 256, nb, dtype=np.uint8)).to(G.DEV) for nb in segs]
+                   for _ in range(3)]
+            live = job.live_of(0)
+
+            def put(e):
+                for t, src in zip(live, pat[e]):
+                    t.copy_(src)
+                torch.cuda.synchronize()
+
+            def check(e, what):
+                job.sync(); torch.cuda.synchronize()
+                for j, (t, src) in enumerate(zip(live, pat[e])):
+                    assert torch.equal(t, src), (what, shift, e, j)
+
+            print(f"[gpu-case] large odd state segments, live shift {shift}", flush=True)
+            put(0); job.ctx_save(0); job.sync()
+            put(1); job.ctx_save(1); job.sync()
+            job.ctx_restore(0); check(0, "restore")
+            put(2)                                  # EST 2's state is live, 0 and 1 are in their slots
+            job.ctx_switch(2, 1); check(1, "switch in")
+            job.ctx_restore(2); check(2, "switch saved the outgoing EST")
+            grad = torch.zeros(64, device=G.DEV)
+            B.check(B.es_est_boundary(job.h, 2, 0, [0], [grad.data_ptr()]), "es_est_boundary", job.h)
+            check(0, "boundary in")
+            put(1)                                  # overwrite live, then bring EST 2 back from its slot
+            job.ctx_restore(2); check(2, "boundary saved the outgoing EST")
+            # the guard bytes around every live tensor are untouched
+            job.sync(); torch.cuda.synchronize()
+            for t in live:
+                assert t.untyped_storage().nbytes() >= t.numel() + 64
+                raw = torch.empty(0, dtype=torch.uint8, device=G.DEV).set_(t.untyped_storage())
+                assert bool((raw[:shift] == 0xEE).all()) and bool((raw[shift + t.numel():] == 0xEE).all()), shift
+        finally:
+            job.close()
